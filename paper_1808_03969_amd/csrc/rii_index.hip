@@ -1,0 +1,322 @@
+// The index handle: device copies of the Rii data structure (Sec. 4.1: linear code array,
+// coarse centres as PQ codes, posting lists of identifiers), data addition and reconfigure
+// (Sec. 4.3, Alg. 4).  Everything here is offline and synchronous.
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <unordered_set>
+#include <string>
+#include <vector>
+
+#include "rii_internal.h"
+
+extern "C" int rii_internal_sym_table(const rii_index* idx, hipStream_t st);
+extern "C" int rii_internal_gather_rows(const uint8_t* codes, const int32_t* list_ids, int64_t N, int M,
+                                        uint8_t* out, hipStream_t st);
+
+namespace {
+
+template <typename T>
+void free_dev(T*& p) {
+  if (p) (void)hipFree(p);
+  p = nullptr;
+}
+
+void drop_lists(rii_index* idx) {
+  free_dev(idx->d_coarse);
+  free_dev(idx->d_list_off);
+  free_dev(idx->d_list_ids);
+  free_dev(idx->d_assign);
+  free_dev(idx->d_codes_list);
+  idx->h_coarse.clear();
+  idx->h_list_off.clear();
+  idx->K = 0;
+  idx->max_list_len = 0;
+}
+
+// Install lists given on the host (already validated) plus the per-item assignment.
+int install_lists(rii_index* idx, const uint8_t* coarse, int K, const std::vector<int64_t>& off,
+                  const std::vector<int32_t>& ids, const std::vector<int32_t>& assign) {
+  const int64_t N = idx->N;
+  const int M = idx->M;
+  drop_lists(idx);
+  RII_HIP(hipMalloc(&idx->d_coarse, (size_t)K * M));
+  RII_HIP(hipMalloc(&idx->d_list_off, (size_t)(K + 1) * 8));
+  RII_HIP(hipMalloc(&idx->d_list_ids, std::max<size_t>((size_t)N * 4, 4)));
+  RII_HIP(hipMalloc(&idx->d_assign, std::max<size_t>((size_t)N * 4, 4)));
+  RII_HIP(hipMalloc(&idx->d_codes_list, std::max<size_t>((size_t)N * M, 16)));
+  RII_HIP(hipMemcpy(idx->d_coarse, coarse, (size_t)K * M, hipMemcpyHostToDevice));
+  RII_HIP(hipMemcpy(idx->d_list_off, off.data(), (size_t)(K + 1) * 8, hipMemcpyHostToDevice));
+  if (N > 0) {
+    RII_HIP(hipMemcpy(idx->d_list_ids, ids.data(), (size_t)N * 4, hipMemcpyHostToDevice));
+    RII_HIP(hipMemcpy(idx->d_assign, assign.data(), (size_t)N * 4, hipMemcpyHostToDevice));
+    int rc = rii_internal_gather_rows(idx->d_codes, idx->d_list_ids, N, M, idx->d_codes_list, nullptr);
+    if (rc) return rc;
+    RII_HIP(hipDeviceSynchronize());
+  }
+  idx->h_coarse.assign(coarse, coarse + (size_t)K * M);
+  idx->h_list_off = off;
+  idx->K = K;
+  idx->max_list_len = 0;
+  for (int k = 0; k < K; ++k) idx->max_list_len = std::max(idx->max_list_len, off[k + 1] - off[k]);
+  return RII_OK;
+}
+
+// a(n) for rows [first, first+n) of the stored codes under the host coarse centres `coarse`.
+int assign_stored(rii_index* idx, int64_t first, int64_t n, const uint8_t* coarse, int K, int32_t* assign_host) {
+  if (n == 0) return RII_OK;
+  uint8_t* d_coarse = nullptr;
+  int32_t* d_out = nullptr;
+  RII_HIP(hipMalloc(&d_coarse, (size_t)K * idx->M));
+  if (hipMalloc(&d_out, (size_t)n * 4) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(d_coarse);
+    return RII_ERR_OOM;
+  }
+  int rc = RII_OK;
+  if (hipMemcpy(d_coarse, coarse, (size_t)K * idx->M, hipMemcpyHostToDevice) != hipSuccess) rc = RII_ERR_DEVICE;
+  if (!rc) rc = rii_assign(idx, idx->d_codes + first * idx->M, n, d_coarse, K, d_out, nullptr);
+  if (!rc && hipMemcpy(assign_host, d_out, (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
+  (void)hipFree(d_coarse);
+  (void)hipFree(d_out);
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rii_index_create(const float* codebooks, int D, int M, int Ks, rii_index_t** out) {
+  if (!out) return RII_ERR_INVALID_ARG;
+  if (M <= 0 || D <= 0 || D % M != 0 || Ks != RII_KS) return RII_ERR_DIM;
+  if (!codebooks) return RII_ERR_INVALID_ARG;
+  rii_index* idx = new (std::nothrow) rii_index();
+  if (!idx) return RII_ERR_OOM;
+  idx->D = D; idx->M = M; idx->Ks = Ks; idx->Ds = D / M;
+  if (hipGetDevice(&idx->device) != hipSuccess) {
+    (void)hipGetLastError();
+    delete idx;
+    return RII_ERR_DEVICE;
+  }
+  size_t bytes = (size_t)M * Ks * idx->Ds * sizeof(float);
+  if (hipMalloc(&idx->d_cb, bytes) != hipSuccess ||
+      hipMemcpy(idx->d_cb, codebooks, bytes, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipGetLastError();
+    rii_index_destroy(idx);
+    return RII_ERR_DEVICE;
+  }
+  *out = idx;
+  return RII_OK;
+}
+
+void rii_index_destroy(rii_index_t* idx) {
+  if (!idx) return;
+  drop_lists(idx);
+  free_dev(idx->d_cb);
+  free_dev(idx->d_sym);
+  free_dev(idx->d_codes);
+  if (idx->ws) (void)hipFree(idx->ws);
+  delete idx;
+}
+
+int rii_index_set_threshold(rii_index_t* idx, int64_t theta) {
+  if (!idx) return RII_ERR_INVALID_ARG;
+  idx->theta = theta;
+  return RII_OK;
+}
+
+int rii_index_info(const rii_index_t* idx, int64_t* info) {
+  if (!idx || !info) return RII_ERR_INVALID_ARG;
+  const int64_t N = idx->N, M = idx->M, K = idx->K;
+  info[0] = N; info[1] = idx->D; info[2] = M; info[3] = idx->Ks; info[4] = K; info[5] = idx->theta;
+  info[6] = (N + K) * M + 4 * N;
+  int64_t dev = (int64_t)M * 256 * idx->Ds * 4 + idx->cap * M + (int64_t)idx->ws_bytes;
+  if (idx->d_sym) dev += M * 256 * 256 * 4;
+  if (K > 0) dev += K * M + (K + 1) * 8 + N * 4 /*ids*/ + N * 4 /*assign*/ + N * M /*list-ordered codes*/;
+  info[7] = dev;
+  return RII_OK;
+}
+
+int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
+  if (!idx || n < 0 || (n > 0 && !codes) || (mem != RII_MEM_HOST && mem != RII_MEM_DEVICE)) return RII_ERR_INVALID_ARG;
+  if (idx->M % 4 != 0) return RII_ERR_UNSUPPORTED;
+  if (n == 0) return RII_OK;
+  if (idx->N + n > 2147483647LL) return RII_ERR_UNSUPPORTED;
+  const int M = idx->M;
+  if (idx->N + n > idx->cap) {
+    int64_t ncap = std::max<int64_t>(idx->N + n, idx->cap + idx->cap / 2);
+    uint8_t* nb = nullptr;
+    if (hipMalloc(&nb, (size_t)ncap * M) != hipSuccess) {
+      (void)hipGetLastError();
+      ncap = idx->N + n;
+      RII_HIP(hipMalloc(&nb, (size_t)ncap * M));
+    }
+    if (idx->N > 0) RII_HIP(hipMemcpy(nb, idx->d_codes, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
+    free_dev(idx->d_codes);
+    idx->d_codes = nb;
+    idx->cap = ncap;
+  }
+  RII_HIP(hipMemcpy(idx->d_codes + idx->N * M, codes, (size_t)n * M,
+                    mem == RII_MEM_HOST ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice));
+  const int64_t oldN = idx->N;
+  idx->N += n;
+  if (idx->K > 0) {
+    // push every new identifier to the list of its nearest coarse centre; lists stay ascending
+    // because new identifiers are larger than all stored ones
+    std::vector<int32_t> assign(idx->N);
+    if (oldN > 0) RII_HIP(hipMemcpy(assign.data(), idx->d_assign, (size_t)oldN * 4, hipMemcpyDeviceToHost));
+    std::vector<uint8_t> coarse = idx->h_coarse;
+    const int K = idx->K;
+    int rc = assign_stored(idx, oldN, n, coarse.data(), K, assign.data() + oldN);
+    if (rc) return rc;
+    std::vector<int64_t> off;
+    std::vector<int32_t> ids;
+    rc = rii_host::build_csr(assign.data(), idx->N, K, off, ids);
+    if (rc) return rc;
+    return install_lists(idx, coarse.data(), K, off, ids, assign);
+  }
+  return RII_OK;
+}
+
+int rii_index_set_lists(rii_index_t* idx, const uint8_t* coarse, int K, const int64_t* list_offsets,
+                        const int32_t* list_ids, int mem) {
+  if (!idx || !coarse || !list_offsets || K < 1 || (mem != RII_MEM_HOST && mem != RII_MEM_DEVICE))
+    return RII_ERR_INVALID_ARG;
+  const int64_t N = idx->N;
+  if (N > 0 && !list_ids) return RII_ERR_INVALID_ARG;
+  std::vector<uint8_t> hc((size_t)K * idx->M);
+  std::vector<int64_t> off(K + 1);
+  std::vector<int32_t> ids(N);
+  hipMemcpyKind kind = mem == RII_MEM_HOST ? hipMemcpyHostToHost : hipMemcpyDeviceToHost;
+  RII_HIP(hipMemcpy(hc.data(), coarse, hc.size(), kind));
+  RII_HIP(hipMemcpy(off.data(), list_offsets, (size_t)(K + 1) * 8, kind));
+  if (N > 0) RII_HIP(hipMemcpy(ids.data(), list_ids, (size_t)N * 4, kind));
+  if (off[0] != 0 || off[K] != N) return RII_ERR_INVALID_ARG;
+  std::vector<int32_t> assign(N, -1);
+  for (int k = 0; k < K; ++k) {
+    if (off[k + 1] < off[k]) return RII_ERR_INVALID_ARG;
+    for (int64_t p = off[k]; p < off[k + 1]; ++p) {
+      int32_t n = ids[p];
+      if (n < 0 || n >= N || assign[n] != -1) return RII_ERR_UNSORTED_IDS;
+      if (p > off[k] && ids[p - 1] >= n) return RII_ERR_UNSORTED_IDS;
+      assign[n] = k;
+    }
+  }
+  return install_lists(idx, hc.data(), K, off, ids, assign);
+}
+
+int rii_index_build_lists(rii_index_t* idx, const uint8_t* coarse, int K) {
+  if (!idx || !coarse || K < 1) return RII_ERR_INVALID_ARG;
+  std::vector<int32_t> assign(idx->N);
+  int rc = assign_stored(idx, 0, idx->N, coarse, K, assign.data());
+  if (rc) return rc;
+  std::vector<int64_t> off;
+  std::vector<int32_t> ids;
+  rc = rii_host::build_csr(assign.data(), idx->N, K, off, ids);
+  if (rc) return rc;
+  return install_lists(idx, coarse, K, off, ids, assign);
+}
+
+int rii_index_reconfigure(rii_index_t* idx, int K, int iters, uint64_t seed) {
+  if (!idx || K < 1 || iters < 0 || idx->N < K) return RII_ERR_INVALID_ARG;
+  const int M = idx->M;
+  const int64_t N = idx->N;
+  // sample of at most min(N, 100 K) stored codes (Sec. 4.3)
+  const int64_t ns = std::min<int64_t>(N, (int64_t)100 * K);
+  std::vector<int64_t> rows = rii_host::sample_without_replacement(N, ns, seed);
+  std::vector<uint8_t> sample((size_t)ns * M);
+  {
+    // fetch the sampled rows: whole array when the sample is dense, row by row otherwise
+    if (ns * 4 >= N) {
+      std::vector<uint8_t> all((size_t)N * M);
+      RII_HIP(hipMemcpy(all.data(), idx->d_codes, all.size(), hipMemcpyDeviceToHost));
+      for (int64_t i = 0; i < ns; ++i) std::memcpy(&sample[i * M], &all[rows[i] * M], M);
+    } else {
+      std::vector<int32_t> r32(rows.begin(), rows.end());
+      int32_t* d_rows = nullptr;
+      uint8_t* d_tmp = nullptr;
+      RII_HIP(hipMalloc(&d_rows, (size_t)ns * 4));
+      RII_HIP(hipMalloc(&d_tmp, (size_t)ns * M));
+      RII_HIP(hipMemcpy(d_rows, r32.data(), (size_t)ns * 4, hipMemcpyHostToDevice));
+      int rc = rii_internal_gather_rows(idx->d_codes, d_rows, ns, M, d_tmp, nullptr);
+      if (rc) return rc;
+      RII_HIP(hipMemcpy(sample.data(), d_tmp, sample.size(), hipMemcpyDeviceToHost));
+      (void)hipFree(d_rows);
+      (void)hipFree(d_tmp);
+    }
+  }
+  // initial centres: the first K distinct codes of the sample in a seeded order
+  std::vector<uint8_t> coarse((size_t)K * M);
+  {
+    std::vector<int64_t> order(ns);
+    for (int64_t i = 0; i < ns; ++i) order[i] = i;
+    std::sort(order.begin(), order.end(), [&](int64_t a, int64_t b) {
+      uint64_t ha = rii_host::mix64(seed ^ (uint64_t)rows[a] * 0x9E3779B97F4A7C15ull);
+      uint64_t hb = rii_host::mix64(seed ^ (uint64_t)rows[b] * 0x9E3779B97F4A7C15ull);
+      return ha != hb ? ha < hb : a < b;
+    });
+    std::unordered_set<std::string> seen;
+    int got = 0;
+    for (int64_t i = 0; i < ns && got < K; ++i) {
+      std::string key(reinterpret_cast<const char*>(&sample[order[i] * M]), M);
+      if (seen.insert(key).second) {
+        std::memcpy(&coarse[(size_t)got * M], key.data(), M);
+        ++got;
+      }
+    }
+    for (int64_t i = 0; got < K; ++i, ++got)  // fewer than K distinct codes: repeat sample rows
+      std::memcpy(&coarse[(size_t)got * M], &sample[order[i % ns] * M], M);
+  }
+  if (iters > 0) {
+    int rc = rii_internal_sym_table(idx, nullptr);
+    if (rc) return rc;
+    std::vector<float> sym((size_t)M * 256 * 256);
+    RII_HIP(hipDeviceSynchronize());
+    RII_HIP(hipMemcpy(sym.data(), idx->d_sym, sym.size() * 4, hipMemcpyDeviceToHost));
+    uint8_t* d_sample = nullptr;
+    uint8_t* d_coarse = nullptr;
+    int32_t* d_assign = nullptr;
+    RII_HIP(hipMalloc(&d_sample, (size_t)ns * M));
+    RII_HIP(hipMalloc(&d_coarse, (size_t)K * M));
+    RII_HIP(hipMalloc(&d_assign, (size_t)ns * 4));
+    RII_HIP(hipMemcpy(d_sample, sample.data(), sample.size(), hipMemcpyHostToDevice));
+    std::vector<int32_t> assign(ns);
+    for (int it = 0; it < iters; ++it) {
+      RII_HIP(hipMemcpy(d_coarse, coarse.data(), coarse.size(), hipMemcpyHostToDevice));
+      int rc2 = rii_assign(idx, d_sample, ns, d_coarse, K, d_assign, nullptr);
+      if (rc2) return rc2;
+      RII_HIP(hipMemcpy(assign.data(), d_assign, (size_t)ns * 4, hipMemcpyDeviceToHost));
+      rii_host::update_centres(sample.data(), ns, assign.data(), sym.data(), M, K, coarse.data());
+    }
+    (void)hipFree(d_sample);
+    (void)hipFree(d_coarse);
+    (void)hipFree(d_assign);
+  }
+  return rii_index_build_lists(idx, coarse.data(), K);
+}
+
+int rii_index_get_lists(const rii_index_t* idx, uint8_t* coarse_out, int64_t* list_offsets_out,
+                        int32_t* list_ids_out, int32_t* assign_out, int mem) {
+  if (!idx || (mem != RII_MEM_HOST && mem != RII_MEM_DEVICE)) return RII_ERR_INVALID_ARG;
+  if (idx->K < 1) return RII_ERR_NOT_BUILT;
+  hipMemcpyKind kind = mem == RII_MEM_HOST ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice;
+  if (coarse_out) RII_HIP(hipMemcpy(coarse_out, idx->d_coarse, (size_t)idx->K * idx->M, kind));
+  if (list_offsets_out) RII_HIP(hipMemcpy(list_offsets_out, idx->d_list_off, (size_t)(idx->K + 1) * 8, kind));
+  if (list_ids_out && idx->N) RII_HIP(hipMemcpy(list_ids_out, idx->d_list_ids, (size_t)idx->N * 4, kind));
+  if (assign_out && idx->N) RII_HIP(hipMemcpy(assign_out, idx->d_assign, (size_t)idx->N * 4, kind));
+  return RII_OK;
+}
+
+int rii_index_get_codes(const rii_index_t* idx, int64_t first, int64_t n, uint8_t* codes_out, int mem) {
+  if (!idx || first < 0 || n < 0 || first + n > idx->N || (n > 0 && !codes_out) ||
+      (mem != RII_MEM_HOST && mem != RII_MEM_DEVICE))
+    return RII_ERR_INVALID_ARG;
+  if (n == 0) return RII_OK;
+  RII_HIP(hipMemcpy(codes_out, idx->d_codes + first * idx->M, (size_t)n * idx->M,
+                    mem == RII_MEM_HOST ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice));
+  return RII_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+// Internal declarations shared by the translation units of the library (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "rii.h"
+
+struct rii_index {
+  int D = 0, M = 0, Ks = 0, Ds = 0;
+  int device = 0;
+  int64_t N = 0;         // stored codes
+  int64_t cap = 0;       // rows allocated in d_codes
+  int K = 0;             // coarse centres (0: no posting lists)
+  int64_t theta = 0;     // switch threshold of the query procedure
+
+  float* d_cb = nullptr;          // [M][256][Ds] codebooks
+  float* d_sym = nullptr;         // [M][256][256] code-word-to-code-word squared distances (lazy)
+  uint8_t* d_codes = nullptr;     // [cap][M] codes in identifier order (the linear array)
+  uint8_t* d_coarse = nullptr;    // [K][M] coarse centres (PQ codes)
+  int64_t* d_list_off = nullptr;  // [K+1]
+  int32_t* d_list_ids = nullptr;  // [N] identifiers, list after list
+  int32_t* d_assign = nullptr;    // [N] a(n)
+  uint8_t* d_codes_list = nullptr;  // [N][M] codes permuted into list order (row p = code of d_list_ids[p])
+  std::vector<uint8_t> h_coarse;    // host mirror of the coarse centres
+  std::vector<int64_t> h_list_off;  // host mirror of the list offsets
+  int64_t max_list_len = 0;
+
+  // scratch reused by the online calls (grown on demand)
+  mutable void* ws = nullptr;
+  mutable size_t ws_bytes = 0;
+};
+
+#define RII_HIP(call)                         \
+  do {                                        \
+    hipError_t e__ = (call);                  \
+    if (e__ != hipSuccess) {                  \
+      (void)hipGetLastError();                \
+      return e__ == hipErrorOutOfMemory ? RII_ERR_OOM : RII_ERR_DEVICE; \
+    }                                         \
+  } while (0)
+
+// host-side helpers implemented in rii_host.cpp
+namespace rii_host {
+uint64_t mix64(uint64_t z);
+// n distinct values from [0, N), ascending; seeded.
+std::vector<int64_t> sample_without_replacement(int64_t N, int64_t n, uint64_t seed);
+// one update round of the code-space clustering used by reconfigure (see rii.h)
+void update_centres(const uint8_t* sample, int64_t n, const int32_t* assign, const float* sym, int M, int K,
+                    uint8_t* coarse);
+// stable grouping of identifiers by list number
+int build_csr(const int32_t* assign, int64_t N, int K, std::vector<int64_t>& off, std::vector<int32_t>& ids);
+}  // namespace rii_host

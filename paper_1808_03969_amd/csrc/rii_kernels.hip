@@ -1,0 +1,945 @@
+// HIP kernels (gfx950) and the device-side entry points of the library.
+//
+// Data flow of one query batch:
+//   k_build_lut        q, codebooks                       -> A [Q][M][256]          (Sec. 3)
+//   k_scan<LINEAR>     A in LDS, codes streamed           -> per-block top-R keys   (Alg. 1, whole data)
+//   k_scan<SUBSET>     A in LDS, codes gathered by id     -> per-block top-R keys   (Alg. 1, subset)
+//   k_ivf              A in LDS, probed lists streamed    -> top-R                  (Alg. 2, second block)
+//   k_select           keys / candidates                  -> top-R sorted           (PartialSort + Take)
+//
+// A candidate is one 64-bit key: order-preserving image of the fp32 distance in the high word,
+// identifier in the low word.  Comparing keys as unsigned integers is the (distance,
+// identifier) order, so selection is exact and deterministic including ties.
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "rii_internal.h"
+
+namespace {
+
+constexpr int kSelCap = 2048;          // keys held per block between compactions (2 * RII_MAX_TOPK)
+constexpr int kScanThreads = 1024;
+constexpr int kRowsPerLane = 4;        // rows scored per lane between two block barriers
+constexpr uint64_t kKeyMax = ~0ull;
+constexpr uint32_t kOrdMax = 0xFFFFFFFFu;
+
+// ------------------------------------------------------------------ keys
+__device__ __forceinline__ uint32_t ord_of(float d) {
+  uint32_t b = __float_as_uint(d);
+  return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float float_of_ord(uint32_t o) {
+  uint32_t b = o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu);
+  return __uint_as_float(b);
+}
+__device__ __forceinline__ uint64_t make_key(float d, int32_t id) {
+  return ((uint64_t)ord_of(d) << 32) | (uint32_t)id;
+}
+
+// ------------------------------------------------------------------ block-level selection
+// keys[0..kSelCap) in LDS, *cnt entries used, *tau = largest distance image still of interest.
+
+__device__ __forceinline__ int next_pow2(int v) {
+  int p = 2;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+// Ascending bitonic sort of keys[0..n2), n2 a power of two.  Block-wide; ends with a barrier.
+__device__ void block_bitonic_sort(uint64_t* keys, int n2) {
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  for (int size = 2; size <= n2; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < (n2 >> 1); t += nthr) {
+        int i = 2 * t - (t & (stride - 1));
+        int j = i + stride;
+        bool up = ((i & size) == 0);
+        uint64_t a = keys[i], b = keys[j];
+        if ((a > b) == up) {
+          keys[i] = b;
+          keys[j] = a;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Keep the k smallest keys (sorted ascending) and tighten *tau.  Must be entered by all threads
+// after a barrier that follows the last push.
+__device__ void sel_compact(uint64_t* keys, int* cnt, uint32_t* tau, int k) {
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  int c = *cnt;
+  if (c > kSelCap) c = kSelCap;
+  int n2 = next_pow2(c);
+  for (int i = c + tid; i < n2; i += nthr) keys[i] = kKeyMax;
+  __syncthreads();
+  block_bitonic_sort(keys, n2);
+  if (tid == 0) {
+    *cnt = c < k ? c : k;
+    if (c >= k) {
+      uint32_t t = (uint32_t)(keys[k - 1] >> 32);
+      if (t < *tau) *tau = t;
+    }
+  }
+  __syncthreads();
+}
+
+// Offer up to R keys per thread (bit r of `pend` set: key[r] is a candidate).  Block-wide:
+// every thread of the block must call it, the same number of times.  Returns true when a
+// compaction happened (tau may have changed).
+template <int R>
+__device__ bool sel_offer(uint64_t* keys, int* cnt, uint32_t* tau, int k, const uint64_t (&key)[R], uint32_t pend) {
+  bool compacted = false;
+  while (__syncthreads_or((int)pend)) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (pend & (1u << r)) {
+        int idx = atomicAdd(cnt, 1);
+        if (idx < kSelCap) {
+          keys[idx] = key[r];
+          pend &= ~(1u << r);
+        }
+      }
+    }
+    __syncthreads();
+    if (*cnt >= kSelCap) {  // uniform: nobody changes *cnt before the next barrier
+      sel_compact(keys, cnt, tau, k);
+      compacted = true;
+      uint32_t t = *tau;
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if ((pend & (1u << r)) && (uint32_t)(key[r] >> 32) > t) pend &= ~(1u << r);
+    }
+  }
+  return compacted;
+}
+
+// ------------------------------------------------------------------ distance tables (Sec. 3)
+// grid (M, Q), block 256: thread z computes A(m, z) for query blockIdx.y.
+__global__ void k_build_lut(const float* __restrict__ cb, const float* __restrict__ q, int D, int M, int Ds,
+                            float* __restrict__ lut) {
+  const int m = blockIdx.x, z = threadIdx.x;
+  const int64_t qi = blockIdx.y;
+  const float* qs = q + qi * D + m * Ds;
+  const float* c = cb + ((size_t)m * 256 + z) * Ds;
+  float acc = 0.f;
+  for (int j = 0; j < Ds; ++j) {
+    float diff = __fsub_rn(qs[j], c[j]);
+    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+  }
+  lut[(qi * M + m) * 256 + z] = acc;
+}
+
+// ------------------------------------------------------------------ ADC of one row (Eq. 2)
+// Loads the M code bytes of one row with the widest aligned loads M allows and sums the M
+// table entries in ascending sub-space order.
+template <int MT>
+__device__ __forceinline__ float adc_row(const float* __restrict__ A, const uint8_t* __restrict__ row, int Mrt) {
+  float d = 0.f;
+  if constexpr (MT == 0) {
+    // run-time M (a multiple of 4)
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(row);
+    for (int j = 0; j < (Mrt >> 2); ++j) {
+      uint32_t v = w[j];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) d = __fadd_rn(d, A[(4 * j + b) * 256 + ((v >> (8 * b)) & 255u)]);
+    }
+  } else if constexpr (MT % 16 == 0) {
+    uint32_t w[MT / 4];
+    const uint4* p = reinterpret_cast<const uint4*>(row);
+#pragma unroll
+    for (int j = 0; j < MT / 16; ++j) {
+      uint4 v = p[j];
+      w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) d = __fadd_rn(d, A[m * 256 + ((w[m >> 2] >> (8 * (m & 3))) & 255u)]);
+  } else {
+    static_assert(MT == 8, "specialised for M = 8, 16, 32, 64");
+    uint2 v = *reinterpret_cast<const uint2*>(row);
+    uint32_t w[2] = {v.x, v.y};
+#pragma unroll
+    for (int m = 0; m < 8; ++m) d = __fadd_rn(d, A[m * 256 + ((w[m >> 2] >> (8 * (m & 3))) & 255u)]);
+  }
+  return d;
+}
+
+// ------------------------------------------------------------------ scan (Alg. 1)
+struct ScanArgs {
+  const uint8_t* codes;          // [N][M]
+  int64_t N;
+  int M;
+  const float* lut;              // [Q][M][256]
+  const int32_t* target_ids;     // subset mode
+  const int64_t* target_offsets; // subset mode, [Q+1]
+  int64_t chunk_rows;            // rows (or targets) per block
+  int k;
+  uint64_t* partial;             // [Q][gridDim.x][k]
+  uint32_t* tau_g;               // [Q] shared distance bound per query
+  const int* qmode;              // optional [Q]; block runs only when qmode[q] == want_mode
+  int want_mode;
+};
+
+enum { kLinear = 0, kSubset = 1 };
+
+template <int MT, int MODE>
+__global__ __launch_bounds__(kScanThreads) void k_scan(ScanArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : a.M;
+  float* A = reinterpret_cast<float*>(smem);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(smem + (size_t)M * 1024);
+  __shared__ int s_cnt;
+  __shared__ uint32_t s_tau;
+
+  const int tid = threadIdx.x;
+  const int64_t q = blockIdx.y;
+  uint64_t* part = a.partial + (q * gridDim.x + blockIdx.x) * a.k;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
+
+  int64_t nrows;
+  const int32_t* tids = nullptr;
+  if (MODE == kLinear) {
+    nrows = a.N;
+  } else {
+    int64_t o0 = a.target_offsets[q];
+    nrows = a.target_offsets[q + 1] - o0;
+    tids = a.target_ids + o0;
+  }
+  const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
+  const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
+  if (r0 >= r1) {
+    for (int i = tid; i < a.k; i += blockDim.x) part[i] = kKeyMax;
+    return;
+  }
+
+  const float* lut = a.lut + q * M * 256;
+  for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
+  if (tid == 0) {
+    s_cnt = 0;
+    s_tau = kOrdMax;
+  }
+  __syncthreads();
+
+  for (int64_t tile = r0; tile < r1; tile += (int64_t)blockDim.x * kRowsPerLane) {
+    uint64_t key[kRowsPerLane];
+    uint32_t pend = 0;
+    uint32_t tau = s_tau;
+    uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tg < tau) tau = tg;
+#pragma unroll
+    for (int r = 0; r < kRowsPerLane; ++r) {
+      int64_t i = tile + (int64_t)r * blockDim.x + tid;
+      key[r] = kKeyMax;
+      if (i < r1) {
+        int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
+        float d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
+        key[r] = make_key(d, id);
+        if ((uint32_t)(key[r] >> 32) <= tau) pend |= 1u << r;
+      }
+    }
+    if (sel_offer<kRowsPerLane>(keys, &s_cnt, &s_tau, a.k, key, pend)) {
+      if (tid == 0) atomicMin(a.tau_g + q, s_tau);
+    }
+  }
+  __syncthreads();
+  sel_compact(keys, &s_cnt, &s_tau, a.k);
+  if (tid == 0) atomicMin(a.tau_g + q, s_tau);
+  const int c = s_cnt;
+  for (int i = tid; i < a.k; i += blockDim.x) part[i] = i < c ? keys[i] : kKeyMax;
+}
+
+// ------------------------------------------------------------------ PartialSort + Take
+struct SelectArgs {
+  // source A: keys [Q][nkeys] (per-block partial results)
+  const uint64_t* keys;
+  int64_t nkeys;
+  // source B: explicit candidates in CSR segments
+  const float* cand_dist;
+  const int32_t* cand_ids;
+  const int64_t* cand_offsets;
+  int k;
+  int out_stride;      // elements between consecutive queries in ids/dist (>= k)
+  int32_t* ids;
+  float* dist;
+  const int* qmode;
+  int want_mode;
+};
+
+__device__ __forceinline__ void write_result(const uint64_t* keys, int c, int k, int32_t* ids, float* dist) {
+  for (int i = threadIdx.x; i < k; i += blockDim.x) {
+    if (i < c && keys[i] != kKeyMax) {
+      ids[i] = (int32_t)(uint32_t)keys[i];
+      if (dist) dist[i] = float_of_ord((uint32_t)(keys[i] >> 32));
+    } else {
+      ids[i] = -1;
+      if (dist) dist[i] = __uint_as_float(0x7F800000u);
+    }
+  }
+}
+
+// one block per query
+__global__ __launch_bounds__(kScanThreads) void k_select(SelectArgs a) {
+  __shared__ uint64_t keys[kSelCap];
+  __shared__ int s_cnt;
+  __shared__ uint32_t s_tau;
+  const int tid = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
+  if (tid == 0) {
+    s_cnt = 0;
+    s_tau = kOrdMax;
+  }
+  __syncthreads();
+  int64_t n, base = 0;
+  if (a.keys) {
+    n = a.nkeys;
+  } else {
+    base = a.cand_offsets[q];
+    n = a.cand_offsets[q + 1] - base;
+  }
+  for (int64_t t0 = 0; t0 < n; t0 += blockDim.x) {
+    int64_t i = t0 + tid;
+    uint64_t key[1] = {kKeyMax};
+    uint32_t pend = 0;
+    if (i < n) {
+      if (a.keys) key[0] = a.keys[q * a.nkeys + i];
+      else key[0] = make_key(a.cand_dist[base + i], a.cand_ids ? a.cand_ids[base + i] : (int32_t)i);
+      if (key[0] != kKeyMax && (uint32_t)(key[0] >> 32) <= s_tau) pend = 1;
+    }
+    sel_offer<1>(keys, &s_cnt, &s_tau, a.k, key, pend);
+  }
+  __syncthreads();
+  sel_compact(keys, &s_cnt, &s_tau, a.k);
+  write_result(keys, s_cnt, a.k, a.ids + q * a.out_stride, a.dist ? a.dist + q * a.out_stride : nullptr);
+}
+
+// Full sort of short segments (<= RII_MAX_SORT candidates) in LDS; one block per query.
+__global__ __launch_bounds__(kScanThreads) void k_sort_segments(SelectArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint64_t* keys = reinterpret_cast<uint64_t*>(smem);
+  const int64_t q = blockIdx.x;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
+  const int64_t base = a.cand_offsets[q];
+  int n = (int)(a.cand_offsets[q + 1] - base);
+  if (n > RII_MAX_SORT) n = RII_MAX_SORT;  // guarded by the host; never read past the LDS array
+  const int n2 = next_pow2(n);
+  for (int i = threadIdx.x; i < n2; i += blockDim.x)
+    keys[i] = i < n ? make_key(a.cand_dist[base + i], a.cand_ids ? a.cand_ids[base + i] : i) : kKeyMax;
+  __syncthreads();
+  block_bitonic_sort(keys, n2);
+  write_result(keys, n, a.k, a.ids + q * a.out_stride, a.dist ? a.dist + q * a.out_stride : nullptr);
+}
+
+// ------------------------------------------------------------------ plain ADC distances
+// dist[q][i] = ADC of row i for i < nrows; grid (ceil(nrows / block), Q).
+template <int MT>
+__global__ void k_adc_all(const uint8_t* __restrict__ codes, int64_t nrows, int Mrt, const float* __restrict__ lut,
+                          float* __restrict__ dist, const int* qmode, int want_mode) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : Mrt;
+  float* A = reinterpret_cast<float*>(smem);
+  const int64_t q = blockIdx.y;
+  if (qmode && qmode[q] != want_mode) return;
+  for (int i = threadIdx.x; i < M * 256; i += blockDim.x) A[i] = lut[q * M * 256 + i];
+  __syncthreads();
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nrows) dist[q * nrows + i] = adc_row<MT>(A, codes + i * M, M);
+}
+
+// ------------------------------------------------------------------ inverted index (Alg. 2, second block)
+struct IvfArgs {
+  const uint8_t* codes_list;     // [N][M] in list order
+  const int32_t* list_ids;       // [N]
+  const int64_t* list_off;       // [K+1]
+  int M;
+  const float* lut;
+  const int32_t* probe;          // [Q][probe_stride]
+  int probe_stride;
+  int nprobe;                    // uniform number of lists ...
+  const int* nprobe_q;           // ... or per query when not NULL
+  const int32_t* target_ids;     // optional filter
+  const int64_t* target_offsets;
+  int64_t Lcap;                  // 0: none
+  int k;
+  int32_t* ids;
+  float* dist;
+  const int* qmode;
+  int want_mode;
+};
+
+__device__ __forceinline__ bool is_member(const int32_t* S, int64_t nS, int32_t n) {
+  int64_t lo = 0, hi = nS;
+  while (lo < hi) {
+    int64_t mid = lo + ((hi - lo) >> 1);
+    if (S[mid] < n) lo = mid + 1; else hi = mid;
+  }
+  return lo < nS && S[lo] == n;
+}
+
+// Exclusive prefix count of `flag` over the block in thread order, and the block total.
+__device__ __forceinline__ int block_rank(bool flag, int* s_wave, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  unsigned long long b = __ballot(flag);
+  int within = __popcll(b & ((1ull << lane) - 1ull));
+  if (lane == 0) s_wave[wave] = __popcll(b);
+  __syncthreads();
+  int before = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) {
+    int c = s_wave[w];
+    if (w < wave) before += c;
+    tot += c;
+  }
+  __syncthreads();
+  *total = tot;
+  return before + within;
+}
+
+template <int MT>
+__global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : a.M;
+  float* A = reinterpret_cast<float*>(smem);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(smem + (size_t)M * 1024);
+  __shared__ int s_cnt;
+  __shared__ uint32_t s_tau;
+  __shared__ int s_wave[kScanThreads / 64];
+
+  const int tid = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
+  for (int i = tid; i < M * 256; i += blockDim.x) A[i] = a.lut[q * M * 256 + i];
+  if (tid == 0) {
+    s_cnt = 0;
+    s_tau = kOrdMax;
+  }
+  __syncthreads();
+
+  const int32_t* S = nullptr;
+  int64_t nS = 0;
+  if (a.target_ids) {
+    int64_t o0 = a.target_offsets[q];
+    S = a.target_ids + o0;
+    nS = a.target_offsets[q + 1] - o0;
+  }
+  const int np = a.nprobe_q ? a.nprobe_q[q] : a.nprobe;
+  int64_t taken = 0;
+  bool done = false;
+  for (int p = 0; p < np && !done; ++p) {
+    const int list = a.probe[q * a.probe_stride + p];
+    const int64_t b = a.list_off[list], e = a.list_off[list + 1];
+    for (int64_t t0 = b; t0 < e && !done; t0 += blockDim.x) {
+      const int64_t pos = t0 + tid;
+      bool valid = pos < e;
+      int32_t id = valid ? a.list_ids[pos] : -1;
+      if (valid && S) valid = is_member(S, nS, id);
+      if (a.Lcap > 0) {
+        int tot;
+        int rank = block_rank(valid, s_wave, &tot);
+        if (taken + rank >= a.Lcap) valid = false;
+        taken += tot;
+        if (taken >= a.Lcap) done = true;  // uniform
+      }
+      uint64_t key[1] = {kKeyMax};
+      uint32_t pend = 0;
+      if (valid) {
+        float d = adc_row<MT>(A, a.codes_list + pos * M, M);
+        key[0] = make_key(d, id);
+        if ((uint32_t)(key[0] >> 32) <= s_tau) pend = 1;
+      }
+      sel_offer<1>(keys, &s_cnt, &s_tau, a.k, key, pend);
+    }
+  }
+  __syncthreads();
+  sel_compact(keys, &s_cnt, &s_tau, a.k);
+  write_result(keys, s_cnt, a.k, a.ids + q * a.k, a.dist ? a.dist + q * a.k : nullptr);
+}
+
+// ------------------------------------------------------------------ small utility kernels
+__global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// Per-query plan of the query procedure (Alg. 3): mode 0 = linear scan, 1 = inverted index;
+// number of lists ceil(K L / |S|) capped at K and at pmax.
+__global__ void k_plan(const int64_t* target_offsets, int64_t N, int Q, int64_t theta, int K, int64_t L, int pmax,
+                       int* qmode, int* nprobe_q) {
+  int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= Q) return;
+  int64_t sz = target_offsets ? target_offsets[q + 1] - target_offsets[q] : N;
+  int mode = (K > 0 && sz >= theta) ? 1 : 0;
+  qmode[q] = mode;
+  int64_t p = 1;
+  if (mode == 1) {
+    p = sz > 0 ? ((int64_t)K * L + sz - 1) / sz : K;  // K, L, sz < 2^31: no overflow
+    if (p > K) p = K;
+    if (p > pmax) p = pmax;
+    if (p < 1) p = 1;
+  }
+  nprobe_q[q] = (int)p;
+}
+
+// Segment offsets i * len for i = 0..Q.
+__global__ void k_iota_offsets(int64_t* off, int Q, int64_t len) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i <= Q) off[i] = (int64_t)i * len;
+}
+
+// ------------------------------------------------------------------ offline kernels
+// Eq. (1): grid (ceil(n / 256), M), block 256; thread = one vector, block = one sub-space.
+__global__ void k_encode(const float* __restrict__ cb, const float* __restrict__ x, int64_t n, int D, int M, int Ds,
+                         uint8_t* __restrict__ codes) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  float* c = reinterpret_cast<float*>(smem);        // [256][Ds]
+  float* xs = c + 256 * Ds;                          // [Ds][256]
+  const int m = blockIdx.y, tid = threadIdx.x;
+  for (int i = tid; i < 256 * Ds; i += blockDim.x) c[i] = cb[(size_t)m * 256 * Ds + i];
+  const int64_t row = (int64_t)blockIdx.x * blockDim.x + tid;
+  if (row < n)
+    for (int j = 0; j < Ds; ++j) xs[j * 256 + tid] = x[row * D + m * Ds + j];
+  __syncthreads();
+  if (row >= n) return;
+  int best = 0;
+  float bestd = 0.f;
+  for (int z = 0; z < 256; ++z) {
+    float acc = 0.f;
+    for (int j = 0; j < Ds; ++j) {
+      float diff = __fsub_rn(xs[j * 256 + tid], c[z * Ds + j]);
+      acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+    }
+    if (z == 0 || acc < bestd) {
+      bestd = acc;
+      best = z;
+    }
+  }
+  codes[row * M + m] = (uint8_t)best;
+}
+
+// Symmetric table: sym[m][i][j] = squared distance between code words i and j of codebook m.
+// grid (256, M), block 256.
+__global__ void k_sym_table(const float* __restrict__ cb, int Ds, float* __restrict__ sym) {
+  const int m = blockIdx.y, i = blockIdx.x, j = threadIdx.x;
+  const float* a = cb + ((size_t)m * 256 + i) * Ds;
+  const float* b = cb + ((size_t)m * 256 + j) * Ds;
+  float acc = 0.f;
+  for (int t = 0; t < Ds; ++t) {
+    float diff = __fsub_rn(a[t], b[t]);
+    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+  }
+  sym[((size_t)m * 256 + i) * 256 + j] = acc;
+}
+
+// a(n): one block per item at a time (grid-stride over items).  The item's M table rows
+// sym[m][code_n[m]][.] act as its distance table; the coarse codes are scanned with it and
+// the arg-min (lowest k on ties) is reduced over the block.
+template <int MT>
+__global__ __launch_bounds__(256) void k_assign(const float* __restrict__ sym, const uint8_t* __restrict__ codes,
+                                                int64_t n, int Mrt, const uint8_t* __restrict__ coarse, int K,
+                                                int32_t* __restrict__ assign) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : Mrt;
+  float* A = reinterpret_cast<float*>(smem);  // [M][256]
+  __shared__ uint64_t s_best[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int64_t item = blockIdx.x; item < n; item += gridDim.x) {
+    __syncthreads();
+    for (int i = tid; i < M * 256; i += blockDim.x) {
+      int m = i >> 8, z = i & 255;
+      A[i] = sym[((size_t)m * 256 + codes[item * M + m]) * 256 + z];
+    }
+    __syncthreads();
+    uint64_t best = kKeyMax;
+    for (int k = tid; k < K; k += blockDim.x) {
+      uint64_t key = make_key(adc_row<MT>(A, coarse + (size_t)k * M, M), k);
+      if (key < best) best = key;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      uint64_t other = __shfl_xor(best, o, 64);
+      if (other < best) best = other;
+    }
+    if (lane == 0) s_best[wave] = best;
+    __syncthreads();
+    if (tid == 0) {
+      uint64_t b = s_best[0];
+      for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
+        if (s_best[w] < b) b = s_best[w];
+      assign[item] = (int32_t)(uint32_t)b;
+    }
+  }
+}
+
+// codes_list[p] = codes[list_ids[p]]
+__global__ void k_gather_rows(const uint8_t* __restrict__ codes, const int32_t* __restrict__ list_ids, int64_t N,
+                              int M4, uint32_t* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one dword of one row
+  if (i >= N * M4) return;
+  int64_t p = i / M4;
+  int w = (int)(i - p * M4);
+  out[i] = reinterpret_cast<const uint32_t*>(codes)[(int64_t)list_ids[p] * M4 + w];
+}
+
+// ------------------------------------------------------------------ host helpers
+int ensure_ws(const rii_index* idx, size_t bytes) {
+  if (idx->ws_bytes >= bytes) return RII_OK;
+  if (idx->ws) (void)hipFree(idx->ws);
+  idx->ws = nullptr;
+  idx->ws_bytes = 0;
+  size_t want = bytes + bytes / 4;
+  hipError_t e = hipMalloc(&idx->ws, want);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    e = hipMalloc(&idx->ws, bytes);
+    want = bytes;
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      return RII_ERR_OOM;
+    }
+  }
+  idx->ws_bytes = want;
+  return RII_OK;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool m_supported(int M) { return M >= 4 && M <= RII_MAX_M && M % 4 == 0; }
+
+template <typename Kern>
+int set_lds(Kern kern, size_t bytes) {
+  if (bytes > 48 * 1024) RII_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return RII_OK;
+}
+
+#define DISPATCH_M(M, ...)                                  \
+  switch (M) {                                              \
+    case 8: { constexpr int MT = 8; __VA_ARGS__; } break;   \
+    case 16: { constexpr int MT = 16; __VA_ARGS__; } break; \
+    case 32: { constexpr int MT = 32; __VA_ARGS__; } break; \
+    case 64: { constexpr int MT = 64; __VA_ARGS__; } break; \
+    default: { constexpr int MT = 0; __VA_ARGS__; } break;  \
+  }
+
+// Scan `nrows_max` rows per query (linear: the whole array) and leave per-block partial keys in
+// the workspace; then select.  Workspace layout: [tau Q u32][partial Q*nchunks*k u64].
+int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const float* lut, int Q, int mode,
+                const int32_t* target_ids, const int64_t* target_offsets, int64_t max_rows, int topk,
+                int32_t* ids, float* dist, int out_stride, const int* qmode, int want_mode, void* ws_base,
+                hipStream_t st) {
+  const int M = idx->M;
+  const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
+  // enough blocks to fill the chip several times over, but chunks of at least 16 tiles
+  int64_t want_chunks = (4096 + Q - 1) / Q;
+  int64_t max_chunks = (max_rows + 16 * tile - 1) / (16 * tile);
+  if (max_chunks < 1) max_chunks = 1;
+  int64_t nchunks = std::min(want_chunks, max_chunks);
+  if (nchunks > 65535) nchunks = 65535;
+  int64_t chunk_rows = (max_rows + nchunks - 1) / nchunks;
+  chunk_rows = (chunk_rows + tile - 1) / tile * tile;
+  if (chunk_rows < tile) chunk_rows = tile;
+  nchunks = std::max<int64_t>(1, (max_rows + chunk_rows - 1) / chunk_rows);
+
+  uint8_t* base = static_cast<uint8_t*>(ws_base);
+  uint32_t* tau = reinterpret_cast<uint32_t*>(base);
+  uint64_t* partial = reinterpret_cast<uint64_t*>(base + align_up((size_t)Q * 4, 256));
+
+  k_fill_u32<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, kOrdMax);
+  ScanArgs a{};
+  a.codes = codes; a.N = N; a.M = M; a.lut = lut;
+  a.target_ids = target_ids; a.target_offsets = target_offsets;
+  a.chunk_rows = chunk_rows; a.k = topk; a.partial = partial; a.tau_g = tau;
+  a.qmode = qmode; a.want_mode = want_mode;
+  const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
+  dim3 grid((unsigned)nchunks, (unsigned)Q);
+  if (Q > 65535) return RII_ERR_UNSUPPORTED;
+  if (mode == kLinear) {
+    DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kLinear>, lds); if (rc) return rc;
+                    k_scan<MT, kLinear><<<grid, kScanThreads, lds, st>>>(a); });
+  } else {
+    DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kSubset>, lds); if (rc) return rc;
+                    k_scan<MT, kSubset><<<grid, kScanThreads, lds, st>>>(a); });
+  }
+  SelectArgs s{};
+  s.keys = partial; s.nkeys = nchunks * topk; s.k = topk; s.out_stride = out_stride;
+  s.ids = ids; s.dist = dist; s.qmode = qmode; s.want_mode = want_mode;
+  k_select<<<Q, kScanThreads, 0, st>>>(s);
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+size_t scan_ws_bytes(int Q, int64_t max_rows, int topk) {
+  const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
+  int64_t want_chunks = (4096 + Q - 1) / Q;
+  int64_t max_chunks = std::max<int64_t>(1, (max_rows + 16 * tile - 1) / (16 * tile));
+  int64_t nchunks = std::min<int64_t>(std::min(want_chunks, max_chunks), 65535) + 1;
+  return align_up((size_t)Q * 4, 256) + (size_t)Q * nchunks * topk * 8 + 256;
+}
+
+}  // namespace
+
+// ====================================================================== entry points
+extern "C" {
+
+int rii_build_lut(const rii_index_t* idx, const float* q, int Q, float* lut, void* stream) {
+  if (!idx || !q || !lut || Q < 1) return RII_ERR_INVALID_ARG;
+  if (Q > 65535) return RII_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  k_build_lut<<<dim3(idx->M, Q), 256, 0, st>>>(idx->d_cb, q, idx->D, idx->M, idx->Ds, lut);
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_adc_scan_linear(const rii_index_t* idx, const float* lut, int Q, int topk, int32_t* ids, float* dist,
+                        void* stream) {
+  if (!idx || !lut || !ids || !dist || Q < 1 || topk < 1) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
+  if (idx->N < 1) return RII_ERR_INVALID_ARG;
+  int rc = ensure_ws(idx, scan_ws_bytes(Q, idx->N, topk));
+  if (rc) return rc;
+  return launch_scan(idx, idx->d_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
+                     nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
+}
+
+int rii_adc_scan_subset(const rii_index_t* idx, const float* lut, int Q, const int32_t* target_ids,
+                        const int64_t* target_offsets, int64_t max_targets, int topk, int32_t* ids, float* dist,
+                        void* stream) {
+  if (!idx || !lut || !ids || !dist || !target_offsets || Q < 1 || topk < 1 || max_targets < 0)
+    return RII_ERR_INVALID_ARG;
+  if (!target_ids && max_targets > 0) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
+  if (max_targets > idx->N) max_targets = idx->N;
+  int64_t rows = std::max<int64_t>(max_targets, 1);
+  int rc = ensure_ws(idx, scan_ws_bytes(Q, rows, topk));
+  if (rc) return rc;
+  return launch_scan(idx, idx->d_codes, idx->N, lut, Q, kSubset, target_ids, target_offsets, rows, topk, ids, dist,
+                     topk, nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
+}
+
+int rii_topk(const float* cand_dist, const int32_t* cand_ids, const int64_t* cand_offsets, int Q,
+             int64_t max_segment, int topk, int32_t* ids, float* dist, void* stream) {
+  if (!cand_dist || !cand_offsets || !ids || Q < 1 || topk < 1 || max_segment < 0) return RII_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  SelectArgs s{};
+  s.cand_dist = cand_dist; s.cand_ids = cand_ids; s.cand_offsets = cand_offsets;
+  s.k = topk; s.out_stride = topk; s.ids = ids; s.dist = dist;
+  if (topk <= RII_MAX_TOPK) {
+    k_select<<<Q, kScanThreads, 0, st>>>(s);
+  } else {
+    if (topk > RII_MAX_SORT || max_segment < 1 || max_segment > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
+    size_t lds = (size_t)RII_MAX_SORT * 8;
+    int rc = set_lds(k_sort_segments, lds);
+    if (rc) return rc;
+    k_sort_segments<<<Q, kScanThreads, lds, st>>>(s);
+  }
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+// coarse ranking into caller buffers; `ws` must hold what coarse_ws_bytes() says
+static size_t coarse_ws_bytes(const rii_index* idx, int Q, int nprobe) {
+  if (nprobe <= RII_MAX_TOPK) return scan_ws_bytes(Q, idx->K, nprobe);
+  return align_up((size_t)Q * idx->K * 4, 256) + align_up((size_t)(Q + 1) * 8, 256);
+}
+
+static int coarse_rank(const rii_index* idx, const float* lut, int Q, int nprobe, int32_t* list_ids, float* list_d0,
+                       int out_stride, const int* qmode, int want_mode, void* ws, hipStream_t st) {
+  const int M = idx->M, K = idx->K;
+  if (nprobe <= RII_MAX_TOPK) {
+    return launch_scan(idx, idx->d_coarse, K, lut, Q, kLinear, nullptr, nullptr, K, nprobe, list_ids, list_d0,
+                       out_stride, qmode, want_mode, ws, st);
+  }
+  if (K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
+  float* d0 = static_cast<float*>(ws);
+  int64_t* off = reinterpret_cast<int64_t*>(static_cast<uint8_t*>(ws) + align_up((size_t)Q * K * 4, 256));
+  const size_t lds = (size_t)M * 1024;
+  dim3 grid((K + 255) / 256, Q);
+  DISPATCH_M(M, { int rc = set_lds(k_adc_all<MT>, lds); if (rc) return rc;
+                  k_adc_all<MT><<<grid, 256, lds, st>>>(idx->d_coarse, K, M, lut, d0, qmode, want_mode); });
+  k_iota_offsets<<<(Q + 256) / 256, 256, 0, st>>>(off, Q, K);
+  SelectArgs s{};
+  s.cand_dist = d0; s.cand_offsets = off; s.k = nprobe; s.out_stride = out_stride;
+  s.ids = list_ids; s.dist = list_d0; s.qmode = qmode; s.want_mode = want_mode;
+  size_t lds2 = (size_t)RII_MAX_SORT * 8;
+  int rc = set_lds(k_sort_segments, lds2);
+  if (rc) return rc;
+  k_sort_segments<<<Q, kScanThreads, lds2, st>>>(s);
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_coarse_assign(const rii_index_t* idx, const float* lut, int Q, int nprobe, int32_t* list_ids, float* list_d0,
+                      void* stream) {
+  if (!idx || !lut || !list_ids || Q < 1) return RII_ERR_INVALID_ARG;
+  if (idx->K < 1) return RII_ERR_NOT_BUILT;
+  if (nprobe < 1 || nprobe > idx->K) return RII_ERR_INVALID_ARG;
+  if (!m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
+  if (nprobe > RII_MAX_TOPK && idx->K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
+  int rc = ensure_ws(idx, coarse_ws_bytes(idx, Q, nprobe));
+  if (rc) return rc;
+  return coarse_rank(idx, lut, Q, nprobe, list_ids, list_d0, nprobe, nullptr, 0, idx->ws,
+                     static_cast<hipStream_t>(stream));
+}
+
+static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32_t* probe, int probe_stride,
+                      int nprobe, const int* nprobe_q, const int32_t* target_ids, const int64_t* target_offsets,
+                      int64_t L, int topk, int32_t* ids, float* dist, const int* qmode, int want_mode,
+                      hipStream_t st) {
+  const int M = idx->M;
+  IvfArgs a{};
+  a.codes_list = idx->d_codes_list; a.list_ids = idx->d_list_ids; a.list_off = idx->d_list_off; a.M = M;
+  a.lut = lut; a.probe = probe; a.probe_stride = probe_stride; a.nprobe = nprobe; a.nprobe_q = nprobe_q;
+  a.target_ids = target_ids; a.target_offsets = target_offsets; a.Lcap = L; a.k = topk;
+  a.ids = ids; a.dist = dist; a.qmode = qmode; a.want_mode = want_mode;
+  const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
+  DISPATCH_M(M, { int rc = set_lds(k_ivf<MT>, lds); if (rc) return rc;
+                  k_ivf<MT><<<Q, kScanThreads, lds, st>>>(a); });
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_adc_scan_ivf(const rii_index_t* idx, const float* lut, int Q, const int32_t* probe_lists, int nprobe,
+                     const int32_t* target_ids, const int64_t* target_offsets, int64_t L, int topk, int32_t* ids,
+                     float* dist, void* stream) {
+  if (!idx || !lut || !probe_lists || !ids || !dist || Q < 1 || topk < 1 || L < 0) return RII_ERR_INVALID_ARG;
+  if (idx->K < 1) return RII_ERR_NOT_BUILT;
+  if (nprobe < 1 || nprobe > idx->K) return RII_ERR_INVALID_ARG;
+  if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || !m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
+  return launch_ivf(idx, lut, Q, probe_lists, nprobe, nprobe, nullptr, target_ids, target_offsets, L, topk, ids,
+                    dist, nullptr, 0, static_cast<hipStream_t>(stream));
+}
+
+int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int32_t* target_ids,
+              const int64_t* target_offsets, int64_t max_targets, int64_t L, int32_t* ids, float* dist,
+              void* stream) {
+  if (!idx || !q || !ids || !dist || Q < 1 || topk < 1 || L < 1 || max_targets < 0) return RII_ERR_INVALID_ARG;
+  if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
+  if (idx->N < 1) return RII_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int M = idx->M, K = idx->K;
+  const bool has_lists = K > 0;
+  // Largest number of lists any inverted-index query of this batch can ask for: such a query
+  // has |S| >= max(theta, 1).
+  int pmax = 1;
+  if (has_lists) {
+    int64_t smin = std::max<int64_t>(idx->theta, 1);
+    int64_t p = ((int64_t)K * L + smin - 1) / smin;
+    pmax = (int)std::min<int64_t>(p, K);
+    if (pmax > RII_MAX_TOPK && K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
+  }
+  // linear-scan queries have |S| < theta (and at most max_targets, N)
+  int64_t lin_rows = target_ids ? std::min<int64_t>(max_targets, idx->N) : idx->N;
+  if (has_lists && idx->theta > 0) lin_rows = std::min<int64_t>(lin_rows, idx->theta - 1);
+  if (has_lists && idx->theta <= 0) lin_rows = 0;
+  if (!target_ids && has_lists && idx->N >= idx->theta) lin_rows = 0;
+  lin_rows = std::max<int64_t>(lin_rows, 1);
+
+  const size_t lut_b = align_up((size_t)Q * M * 256 * 4, 256);
+  const size_t plan_b = align_up((size_t)Q * 4, 256);
+  const size_t probe_b = align_up((size_t)Q * pmax * 4, 256);
+  const size_t scan_b = align_up(scan_ws_bytes(Q, lin_rows, topk), 256);
+  const size_t coarse_b = has_lists ? align_up(coarse_ws_bytes(idx, Q, pmax), 256) : 0;
+  int rc = ensure_ws(idx, lut_b + 2 * plan_b + probe_b + std::max(scan_b, coarse_b));
+  if (rc) return rc;
+  uint8_t* w = static_cast<uint8_t*>(idx->ws);
+  float* lut = reinterpret_cast<float*>(w); w += lut_b;
+  int* qmode = reinterpret_cast<int*>(w); w += plan_b;
+  int* nprobe_q = reinterpret_cast<int*>(w); w += plan_b;
+  int32_t* probe = reinterpret_cast<int32_t*>(w); w += probe_b;
+  void* stage_ws = w;
+
+  k_build_lut<<<dim3(M, Q), 256, 0, st>>>(idx->d_cb, q, idx->D, M, idx->Ds, lut);
+  k_plan<<<(Q + 255) / 256, 256, 0, st>>>(target_offsets, idx->N, Q, idx->theta, K, L, pmax, qmode, nprobe_q);
+  // linear-scan branch (mode 0)
+  if (target_ids) {
+    rc = launch_scan(idx, idx->d_codes, idx->N, lut, Q, kSubset, target_ids, target_offsets, lin_rows, topk, ids,
+                     dist, topk, qmode, 0, stage_ws, st);
+  } else if (!has_lists || idx->N < idx->theta) {
+    rc = launch_scan(idx, idx->d_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
+                     qmode, 0, stage_ws, st);
+  }
+  if (rc) return rc;
+  // inverted-index branch (mode 1); the scratch of the scan stage is reused in stream order
+  if (has_lists) {
+    rc = coarse_rank(idx, lut, Q, pmax, probe, nullptr, pmax, qmode, 1, stage_ws, st);
+    if (rc) return rc;
+    rc = launch_ivf(idx, lut, Q, probe, pmax, pmax, nprobe_q, target_ids, target_offsets, L, topk, ids, dist, qmode,
+                    1, st);
+    if (rc) return rc;
+  }
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_encode_device(const rii_index_t* idx, const float* x, int64_t n, uint8_t* codes_out, void* stream) {
+  if (!idx || n < 0 || (n > 0 && (!x || !codes_out))) return RII_ERR_INVALID_ARG;
+  if (n == 0) return RII_OK;
+  const int Ds = idx->Ds;
+  size_t lds = (size_t)512 * Ds * 4;
+  if (lds > 160 * 1024) return RII_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = set_lds(k_encode, lds);
+  if (rc) return rc;
+  const int64_t max_rows = (int64_t)1 << 30;
+  for (int64_t r0 = 0; r0 < n; r0 += max_rows) {
+    int64_t cnt = std::min(max_rows, n - r0);
+    dim3 grid((unsigned)((cnt + 255) / 256), (unsigned)idx->M);
+    k_encode<<<grid, 256, lds, st>>>(idx->d_cb, x + r0 * idx->D, cnt, idx->D, idx->M, Ds, codes_out + r0 * idx->M);
+  }
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+// lazily build the symmetric table
+int rii_internal_sym_table(const rii_index* cidx, hipStream_t st) {
+  rii_index* idx = const_cast<rii_index*>(cidx);
+  if (idx->d_sym) return RII_OK;
+  RII_HIP(hipMalloc(&idx->d_sym, (size_t)idx->M * 256 * 256 * 4));
+  k_sym_table<<<dim3(256, idx->M), 256, 0, st>>>(idx->d_cb, idx->Ds, idx->d_sym);
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_assign(const rii_index_t* idx, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,
+               int32_t* assign_out, void* stream) {
+  if (!idx || n < 0 || K < 1 || !coarse || (n > 0 && (!codes || !assign_out))) return RII_ERR_INVALID_ARG;
+  if (!m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
+  if (n == 0) return RII_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = rii_internal_sym_table(idx, st);
+  if (rc) return rc;
+  const int M = idx->M;
+  const size_t lds = (size_t)M * 1024;
+  int blocks = (int)std::min<int64_t>(n, 256 * 16);
+  DISPATCH_M(M, { int rc2 = set_lds(k_assign<MT>, lds); if (rc2) return rc2;
+                  k_assign<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, M, coarse, K, assign_out); });
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+// used by rii_index.hip
+int rii_internal_gather_rows(const uint8_t* codes, const int32_t* list_ids, int64_t N, int M, uint8_t* out,
+                             hipStream_t st) {
+  if (N == 0) return RII_OK;
+  const int M4 = M / 4;
+  int64_t total = N * M4;
+  const int64_t per = (int64_t)1 << 30;
+  // one launch covers at most 2^30 dwords
+  for (int64_t r0 = 0; r0 < N; r0 += per / M4) {
+    int64_t cnt = std::min<int64_t>(per / M4, N - r0);
+    int64_t dw = cnt * M4;
+    k_gather_rows<<<(unsigned)((dw + 255) / 256), 256, 0, st>>>(codes, list_ids + r0, cnt, M4,
+                                                             reinterpret_cast<uint32_t*>(out) + r0 * M4);
+  }
+  (void)total;
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+}  // extern "C"

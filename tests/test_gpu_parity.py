@@ -1,0 +1,346 @@
+"""Parity of the HIP library with the CPU oracle, element by element, through the C ABI.
+
+Bar (written out): identifiers, codes, list numbers bit-exact; fp32 distances within 1e-5
+relative (they are expected to be bit-identical, because both sides add the same fp32 table
+entries in the same order).  Sizes are small enough for the oracle to finish in seconds but
+span several blocks, several tiles per block and a ragged tail.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from helpers import RTOL, check_topk, t2n
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rii():
+    import paper_1808_03969_amd as r
+    r.load_library()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return r
+
+
+def make_index(rii, oracle, N, D, M, K, kind="gaussian", seed=1, iters=4, Q=24):
+    """Data, codebooks (product trainer), codes, coarse codes, oracle-built lists, product handle."""
+    gen = {"gaussian": synth.gaussian, "sift": synth.sift_like, "mixture": synth.mixture}[kind]
+    x = t2n(gen(1000 + seed, 0, N, D))
+    q = t2n(gen(2000 + seed, 0, Q, D))
+    train = x[t2n(synth.sample_rows(3000 + seed, N, min(N, 4000)))]
+    cb = rii.rii_train_codebooks(train, M, iters=iters, seed=4000 + seed)
+    codes = rii.rii_encode(cb, x)
+    coarse = codes[t2n(synth.sample_rows(5000 + seed, N, K))].copy() if K else None
+    d = dict(N=N, D=D, M=M, K=K, x=x, q=q, cb=cb, codes=codes, coarse=coarse)
+    index = rii.Index(cb)
+    index.add(codes)
+    if K:
+        T = oracle.sym_table(cb)
+        a = oracle.assign(T, codes, coarse)
+        off, lids = oracle.build_lists(a, K)
+        index.set_lists(coarse, off, lids)
+        d.update(T=T, a=a, off=off, lids=lids)
+    d["index"] = index
+    d["q_dev"] = torch.from_numpy(q).cuda()
+    d["lut_ref"] = oracle.lut(cb, q)
+    return d
+
+
+@pytest.fixture(scope="module")
+def idx32(rii, oracle_lib):
+    # 70,001 rows: 18 tiles of 4096 rows with a ragged tail, M = 32 (the largest configuration's M)
+    return make_index(rii, oracle_lib, N=70001, D=96, M=32, K=50, kind="mixture", seed=1)
+
+
+@pytest.fixture(scope="module")
+def idx16(rii, oracle_lib):
+    return make_index(rii, oracle_lib, N=150000, D=128, M=16, K=97, kind="sift", seed=2)
+
+
+@pytest.fixture(scope="module")
+def idx8(rii, oracle_lib):
+    # the tiny configuration: N = 10,000, D = 128, M = 8, linear scan, top-10
+    return make_index(rii, oracle_lib, N=10000, D=128, M=8, K=16, kind="gaussian", seed=3, Q=100)
+
+
+def lut_dev(rii, d):
+    return rii.rii_build_lut(d["index"], d["q_dev"])
+
+
+# ---------------------------------------------------------------- encode / tables
+@pytest.mark.parametrize("name", ["idx8", "idx16", "idx32"])
+def test_host_and_device_encode_bit_exact(name, rii, oracle_lib, request):
+    d = request.getfixturevalue(name)
+    ref = oracle_lib.encode(d["cb"], d["x"][:20000])
+    assert np.array_equal(d["codes"][:20000], ref)
+    dev = rii.rii_encode_device(d["index"], torch.from_numpy(d["x"][:20000]).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(t2n(dev), ref)
+    assert np.array_equal(d["index"].get_codes(5, 100), d["codes"][5:105])
+
+
+@pytest.mark.parametrize("name", ["idx8", "idx16", "idx32"])
+def test_lut_bit_exact(name, rii, request):
+    d = request.getfixturevalue(name)
+    lut = lut_dev(rii, d)
+    torch.cuda.synchronize()
+    assert np.array_equal(t2n(lut), d["lut_ref"])
+
+
+# ---------------------------------------------------------------- Alg. 1, whole database
+@pytest.mark.parametrize("name,topk", [("idx8", 10), ("idx16", 100), ("idx32", 100), ("idx32", 1), ("idx16", 1024)])
+def test_linear_scan(name, topk, rii, oracle_lib, request):
+    d = request.getfixturevalue(name)
+    ids, dist = rii.rii_adc_scan_linear(d["index"], lut_dev(rii, d), topk)
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    for i in range(len(d["q"])):
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], topk)
+        check_topk(ids[i], dist[i], ref[0], ref[1], rtol=RTOL)
+        assert np.array_equal(dist[i], ref[1])  # same additions in the same order
+
+
+def test_linear_scan_ties_and_padding(rii, oracle_lib):
+    """Many identical codes (exact distance ties) and fewer rows than topk."""
+    rng = np.random.default_rng(5)
+    cb = rng.normal(size=(8, 256, 4)).astype(np.float32)
+    base = rng.integers(0, 256, size=(37, 8)).astype(np.uint8)
+    codes = np.tile(base, (300, 1))  # 11,100 rows, every code 300 times
+    q = rng.normal(size=(6, 32)).astype(np.float32)
+    index = rii.Index(cb)
+    index.add(codes)
+    lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+    ids, dist = rii.rii_adc_scan_linear(index, lut, 700)
+    torch.cuda.synchronize()
+    A = oracle_lib.lut(cb, q)
+    for i in range(6):
+        ref = oracle_lib.linear_scan(A[i], codes, 700)
+        assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])
+    small = rii.Index(cb)
+    small.add(codes[:5])
+    ids, dist = rii.rii_adc_scan_linear(small, lut, 8)
+    torch.cuda.synchronize()
+    for i in range(6):
+        ref = oracle_lib.linear_scan(A[i], codes[:5], 8)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
+def test_generic_m(rii, oracle_lib):
+    """M = 12 takes the run-time-M code path."""
+    d = make_index(rii, oracle_lib, N=9000, D=48, M=12, K=0, seed=7, Q=5)
+    ids, dist = rii.rii_adc_scan_linear(d["index"], lut_dev(rii, d), 20)
+    torch.cuda.synchronize()
+    for i in range(5):
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], 20)
+        assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])
+
+
+def test_m64(rii, oracle_lib):
+    d = make_index(rii, oracle_lib, N=30000, D=128, M=64, K=0, kind="sift", seed=8, Q=4)
+    ids, dist = rii.rii_adc_scan_linear(d["index"], lut_dev(rii, d), 50)
+    torch.cuda.synchronize()
+    for i in range(4):
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], 50)
+        assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])
+
+
+# ---------------------------------------------------------------- Alg. 1, target identifiers
+@pytest.mark.parametrize("name", ["idx16", "idx32"])
+def test_subset_scan(name, rii, oracle_lib, request):
+    d = request.getfixturevalue(name)
+    N, Q = d["N"], len(d["q"])
+    sizes = [0, 1, 5, 99, 100, 101, 4096, 4097, 30000, N] + [1000 + 37 * i for i in range(Q - 10)]
+    tids, toff = synth.subset_batch(77, N, sizes)
+    ids, dist = rii.rii_adc_scan_subset(d["index"], lut_dev(rii, d), tids.cuda(), toff.cuda(), max(sizes), 100)
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    tids, toff = t2n(tids), t2n(toff)
+    for i in range(Q):
+        S = tids[toff[i]:toff[i + 1]]
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], 100, S=S)
+        check_topk(ids[i], dist[i], ref[0], ref[1])
+        assert np.all(np.isin(ids[i][ids[i] >= 0], S))  # results are members of S (Sec. 5.3)
+    # S = everything is the plain scan
+    full = rii.rii_adc_scan_linear(d["index"], lut_dev(rii, d), 100)
+    torch.cuda.synchronize()
+    assert np.array_equal(ids[9], t2n(full[0])[9])
+
+
+# ---------------------------------------------------------------- Alg. 2
+@pytest.mark.parametrize("name", ["idx8", "idx16", "idx32"])
+def test_coarse_assign(name, rii, oracle_lib, request):
+    d = request.getfixturevalue(name)
+    for P in (1, 7, d["K"]):
+        ks, d0 = rii.rii_coarse_assign(d["index"], lut_dev(rii, d), P)
+        torch.cuda.synchronize()
+        for i in range(len(d["q"])):
+            ref = oracle_lib.coarse_rank(d["lut_ref"][i], d["coarse"], P)
+            assert np.array_equal(t2n(ks)[i], ref[0]) and np.array_equal(t2n(d0)[i], ref[1])
+
+
+def test_coarse_assign_full_sort_path(rii, oracle_lib):
+    """nprobe above the fused-selection limit ranks all K lists with the in-LDS sort."""
+    d = make_index(rii, oracle_lib, N=6000, D=32, M=8, K=1500, seed=9, Q=3)
+    ks, d0 = rii.rii_coarse_assign(d["index"], lut_dev(rii, d), 1500)
+    torch.cuda.synchronize()
+    for i in range(3):
+        ref = oracle_lib.coarse_rank(d["lut_ref"][i], d["coarse"], 1500)
+        assert np.array_equal(t2n(ks)[i], ref[0]) and np.array_equal(t2n(d0)[i], ref[1])
+
+
+@pytest.mark.parametrize("name", ["idx16", "idx32"])
+def test_ivf_scan(name, rii, oracle_lib, request):
+    d = request.getfixturevalue(name)
+    Q, K, N = len(d["q"]), d["K"], d["N"]
+    lut = lut_dev(rii, d)
+    sizes = [N // 3] * Q
+    tids, toff = synth.subset_batch(78, N, sizes)
+    tids_d, toff_d = tids.cuda(), toff.cuda()
+    tids, toff = t2n(tids), t2n(toff)
+    for P in (1, 8, K):
+        probe, _ = rii.rii_coarse_assign(d["index"], lut, P)
+        for use_S, L in ((False, 0), (True, 0), (False, 777), (True, 501)):
+            ids, dist = rii.rii_adc_scan_ivf(d["index"], lut, probe, 100,
+                                             target_ids=tids_d if use_S else None,
+                                             target_offsets=toff_d if use_S else None, L=L)
+            torch.cuda.synchronize()
+            for i in range(Q):
+                S = tids[toff[i]:toff[i + 1]] if use_S else None
+                ref = oracle_lib.inverted_index(d["lut_ref"][i], d["codes"], d["coarse"], d["off"], d["lids"],
+                                                R=100, P=P, S=S, Lcap=L)
+                check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    # all lists, no cap, no filter == the plain scan (Sec. 4.2)
+    probe, _ = rii.rii_coarse_assign(d["index"], lut, K)
+    a = rii.rii_adc_scan_ivf(d["index"], lut, probe, 100)
+    b = rii.rii_adc_scan_linear(d["index"], lut, 100)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ---------------------------------------------------------------- PartialSort + Take
+def test_topk_on_explicit_candidates(rii):
+    g = torch.Generator().manual_seed(3)
+    lens = [0, 1, 50, 1024, 1025, 5000, 16384, 40000]
+    off = torch.zeros(len(lens) + 1, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.tensor(lens), 0)
+    dist = torch.randn(int(off[-1]), generator=g)  # negative values too
+    dist[off[5]:off[5] + 2500] = dist[off[5]]      # a long run of exact ties
+    cid = torch.randperm(int(off[-1]), generator=g).to(torch.int32)
+    for topk in (1, 100, 1024):
+        ids, out = rii.rii_topk(dist.cuda(), cid.cuda(), off.cuda(), topk)
+        torch.cuda.synchronize()
+        for s, n in enumerate(lens):
+            dd, ii = dist[off[s]:off[s + 1]].numpy(), cid[off[s]:off[s + 1]].numpy()
+            order = np.lexsort((ii, dd))[:topk]
+            k = len(order)
+            assert np.array_equal(t2n(ids)[s][:k], ii[order]) and np.array_equal(t2n(out)[s][:k], dd[order])
+            assert np.all(t2n(ids)[s][k:] == -1) and np.all(np.isinf(t2n(out)[s][k:]))
+    # positions as identifiers, and the full-sort path for topk > 1024
+    lens2 = [3000, 16384, 1]
+    off2 = torch.tensor([0, 3000, 19384, 19385], dtype=torch.int64)
+    dist2 = torch.randn(19385, generator=g)
+    ids, out = rii.rii_topk(dist2.cuda(), None, off2.cuda(), 4000, max_segment=16384)
+    torch.cuda.synchronize()
+    for s, n in enumerate(lens2):
+        dd = dist2[off2[s]:off2[s + 1]].numpy()
+        order = np.lexsort((np.arange(n), dd))[:4000]
+        assert np.array_equal(t2n(ids)[s][:len(order)], order)
+        assert np.all(t2n(ids)[s][len(order):] == -1)
+
+
+# ---------------------------------------------------------------- Alg. 3
+@pytest.mark.parametrize("name", ["idx16", "idx32"])
+def test_query_switch(name, rii, oracle_lib, request):
+    d = request.getfixturevalue(name)
+    N, K, Q = d["N"], d["K"], len(d["q"])
+    theta, L, R = 3000, 2 * (N // K), 100
+    d["index"].set_threshold(theta)
+    sizes = [theta - 1, theta, theta + 1, 0, 10, N, N // 2, 200] + [500 * (i + 1) for i in range(Q - 8)]
+    tids, toff = synth.subset_batch(79, N, sizes)
+    ids, dist = rii.rii_query(d["index"], d["q_dev"], R, tids.cuda(), toff.cuda(), max(sizes), L)
+    torch.cuda.synchronize()
+    tids, toff = t2n(tids), t2n(toff)
+    modes = []
+    for i in range(Q):
+        S = tids[toff[i]:toff[i + 1]]
+        ref = oracle_lib.query(d["cb"], d["q"][i], d["codes"], d["coarse"], d["off"], d["lids"], R, L, theta, S=S)
+        modes.append(ref[2])
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    assert modes[:3] == [0, 1, 1] and 0 in modes[3:] and 1 in modes[3:]
+    # whole database
+    ids, dist = rii.rii_query(d["index"], d["q_dev"], R, L=L)
+    torch.cuda.synchronize()
+    for i in range(Q):
+        ref = oracle_lib.query(d["cb"], d["q"][i], d["codes"], d["coarse"], d["off"], d["lids"], R, L, theta)
+        assert ref[2] == 1
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    # theta above N: everything is a linear scan
+    d["index"].set_threshold(N + 1)
+    ids, dist = rii.rii_query(d["index"], d["q_dev"], R, L=L)
+    torch.cuda.synchronize()
+    for i in range(0, Q, 5):
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], R)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    d["index"].set_threshold(0)
+
+
+# ---------------------------------------------------------------- lists, addition, reconfigure
+def test_assign_and_build_lists(rii, oracle_lib, idx16):
+    d = idx16
+    a = rii.rii_assign(d["index"], torch.from_numpy(d["codes"][:30000]).cuda(), torch.from_numpy(d["coarse"]).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(t2n(a), d["a"][:30000])
+    other = rii.Index(d["cb"])
+    other.add(d["codes"][:40000])
+    other.build_lists(d["coarse"])
+    coarse, off, lids, assign = other.get_lists()
+    a_ref = oracle_lib.assign(d["T"], d["codes"][:40000], d["coarse"])
+    off_ref, lids_ref = oracle_lib.build_lists(a_ref, d["K"])
+    assert np.array_equal(assign, a_ref) and np.array_equal(off, off_ref) and np.array_equal(lids, lids_ref)
+    inf = other.info()
+    assert inf["paper_bytes"] == oracle_lib.index_bytes(40000, d["K"], d["M"])
+
+
+def test_add_then_search_then_reconfigure(rii, oracle_lib):
+    """Data addition keeps the lists of the old centres (Sec. 4.3); reconfigure rebuilds them."""
+    d = make_index(rii, oracle_lib, N=20000, D=96, M=16, K=20, kind="mixture", seed=11, Q=8)
+    extra_x = t2n(synth.mixture(6011, 0, 4000, 96, shift=0.5, means_seed=1011))
+    extra = rii.rii_encode(d["cb"], extra_x)
+    d["index"].add(extra)
+    codes = np.concatenate([d["codes"], extra])
+    a = oracle_lib.assign(d["T"], codes, d["coarse"])
+    off, lids = oracle_lib.build_lists(a, 20)
+    _, off_g, lids_g, a_g = d["index"].get_lists()
+    assert np.array_equal(a_g, a) and np.array_equal(off_g, off) and np.array_equal(lids_g, lids)
+    lut = lut_dev(rii, d)
+    probe, _ = rii.rii_coarse_assign(d["index"], lut, 4)
+    ids, dist = rii.rii_adc_scan_ivf(d["index"], lut, probe, 50)
+    torch.cuda.synchronize()
+    for i in range(8):
+        ref = oracle_lib.inverted_index(d["lut_ref"][i], codes, d["coarse"], off, lids, R=50, P=4)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    # reconfigure: deterministic, lists are the oracle's lists for the new centres
+    d["index"].reconfigure(40, iters=3, seed=5)
+    coarse1, off1, lids1, a1 = d["index"].get_lists()
+    d["index"].reconfigure(40, iters=3, seed=5)
+    coarse2, off2, lids2, a2 = d["index"].get_lists()
+    assert np.array_equal(coarse1, coarse2) and np.array_equal(lids1, lids2)
+    a_ref = oracle_lib.assign(d["T"], codes, coarse1)
+    off_ref, lids_ref = oracle_lib.build_lists(a_ref, 40)
+    assert np.array_equal(a1, a_ref) and np.array_equal(off1, off_ref) and np.array_equal(lids1, lids_ref)
+    probe, _ = rii.rii_coarse_assign(d["index"], lut, 6)
+    ids, dist = rii.rii_adc_scan_ivf(d["index"], lut, probe, 50)
+    torch.cuda.synchronize()
+    for i in range(8):
+        ref = oracle_lib.inverted_index(d["lut_ref"][i], codes, coarse1, off1, lids1, R=50, P=6)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
+def test_determinism(rii, idx32):
+    d = idx32
+    lut = lut_dev(rii, d)
+    a = rii.rii_adc_scan_linear(d["index"], lut, 100)
+    b = rii.rii_adc_scan_linear(d["index"], lut, 100)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
