@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the search path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5] [--queries Q] [--n N]
+
+A *step* is one pass of the whole hot path over one batch of Q queries of the chosen
+configuration (default: the 100M-code configuration, the one the headline metric is quoted
+on), with every input already resident in HBM:
+
+    distance tables -> linear ADC scan + top-R -> coarse ranking -> inverted-index scan + top-R
+    -> subset (gathered) scan + top-R -> the Alg. 3 query procedure on the whole database.
+
+It prints ONE JSON line.  `value` is the number of PQ codes scored per second over the whole
+step; `roofline` is the linear-scan kernel (algorithmic bytes M per code and query pass,
+timed with HIP events recorded around that kernel inside the timed steps); `cpu_baseline` is the
+CPU oracle's linear scan timed single-threaded on a bounded sample of the same codes.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """A pair of raw HIP events (created through the HIP runtime torch has loaded)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.start, self.stop = ctypes.c_void_p(), ctypes.c_void_p()
+        assert self.hip.hipEventCreate(ctypes.byref(self.start)) == 0
+        assert self.hip.hipEventCreate(ctypes.byref(self.stop)) == 0
+
+    def elapsed_ms(self) -> float:
+        assert self.hip.hipEventSynchronize(self.stop) == 0
+        ms = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), self.start, self.stop) == 0
+        return float(ms.value)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c4", "c5"])
+    ap.add_argument("--queries", type=int, default=None, help="batch size Q (default: the configuration's)")
+    ap.add_argument("--n", type=int, default=None, help="database size override (for quick runs)")
+    ap.add_argument("--subset", type=int, default=1_000_000, help="|S| of the subset scan")
+    ap.add_argument("--nprobe", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (see DESIGN.md, 'More than one "
+              "GPU'). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1808_03969_amd as rii
+    from paper_1808_03969_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    rii.load_library()
+    torch.cuda.set_device(0)
+    cfg = workloads.CONFIGS[args.workload]
+    t_setup = time.time()
+    w = workloads.build(cfg, log=log, N=args.n, Q=args.queries)
+    index, q, N, Q = w["index"], w["q"], w["N"], w["Q"]
+    M, K, R = cfg.M, cfg.K, cfg.topk
+    S = min(args.subset, N)
+    nprobe = min(args.nprobe, K) if K else 0
+    t0 = time.time()
+    tids, toff = workloads.subsets(cfg, N, Q, S)
+    torch.cuda.synchronize()
+    log(f"{Q} target subsets of size {S} in {time.time() - t0:.1f}s; setup total {time.time() - t_setup:.1f}s")
+    info = index.info()
+    _, list_off, _, _ = index.get_lists() if K else (None, None, None, None)
+    L_query = max(1, nprobe * (N // K)) if K else 1
+    index.set_threshold(0)
+
+    lut = torch.empty((Q, M, 256), dtype=torch.float32, device="cuda")
+    out_lin = (torch.empty((Q, R), dtype=torch.int32, device="cuda"), torch.empty((Q, R), dtype=torch.float32, device="cuda"))
+    out_ivf = (torch.empty_like(out_lin[0]), torch.empty_like(out_lin[1]))
+    out_sub = (torch.empty_like(out_lin[0]), torch.empty_like(out_lin[1]))
+    out_qry = (torch.empty_like(out_lin[0]), torch.empty_like(out_lin[1]))
+    ev = HipEvents()
+    rii.rii_index_set_scan_events(index, ev.start.value, ev.stop.value)
+    stage_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(6)]
+    probe_holder = {}
+
+    def step(timed: bool):
+        se = stage_ev
+        se[0][0].record(); rii.rii_build_lut(index, q, out=lut); se[0][1].record()
+        se[1][0].record(); rii.rii_adc_scan_linear(index, lut, R, out=out_lin); se[1][1].record()
+        if K:
+            se[2][0].record(); probe, _ = rii.rii_coarse_assign(index, lut, nprobe, want_d0=False); se[2][1].record()
+            probe_holder["p"] = probe
+            se[3][0].record(); rii.rii_adc_scan_ivf(index, lut, probe, R, out=out_ivf); se[3][1].record()
+        se[4][0].record(); rii.rii_adc_scan_subset(index, lut, tids, toff, S, R, out=out_sub); se[4][1].record()
+        if K:
+            se[5][0].record(); rii.rii_query(index, q, R, L=L_query, out=out_qry); se[5][1].record()
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    scan_ms, stage_ms = [], np.zeros(6)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+        torch.cuda.synchronize()
+        scan_ms.append(ev.elapsed_ms())
+        for i, (a, b) in enumerate(stage_ev):
+            if K or i in (0, 1, 4):
+                stage_ms[i] += a.elapsed_time(b)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    stage_ms /= args.steps
+    rii.rii_index_set_scan_events(index, None, None)
+
+    # codes scored in one step
+    probed = 0
+    if K:
+        lens = np.diff(list_off)
+        pl = probe_holder["p"].cpu().numpy()
+        probed = int(lens[pl].sum())
+        probed_query = int(np.minimum(lens[pl].sum(axis=1), L_query).sum())
+    scored = Q * N + Q * S + (probed + probed_query + 2 * Q * K if K else 0)
+    value = scored / (ms_per_step * 1e-3)
+
+    # one query per pass: the plain HBM-roofline number for the scan kernel
+    rii.rii_index_set_scan_events(index, ev.start.value, ev.stop.value)
+    single = []
+    for i in range(12):
+        rii.rii_adc_scan_linear(index, lut[i % Q:i % Q + 1], R)
+        torch.cuda.synchronize()
+        single.append(ev.elapsed_ms())
+    rii.rii_index_set_scan_events(index, None, None)
+    single_ms = float(np.mean(single[2:]))
+
+    scan_avg_ms = float(np.mean(scan_ms))
+    alg_bytes = float(Q) * N * M          # M bytes per code and query pass
+    achieved = alg_bytes / (scan_avg_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": f"k_scan<{M},linear>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "launch_ms": round(scan_avg_ms, 3), "algorithmic_bytes_per_launch": alg_bytes,
+        "single_query_pass": {"launch_ms": round(single_ms, 4), "achieved": round(N * M / (single_ms * 1e-3) / 1e9, 1),
+                              "frac": round(N * M / (single_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                              "codes_per_s": round(N / (single_ms * 1e-3), 1)},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle  # the CPU oracle, timed beside the GPU path (never used by it)
+        n_s = min(N, 25_000_000)
+        codes_h = index.get_codes(0, n_s)
+        A = lut[:2].cpu().numpy()
+        got_i, got_d = out_lin[0][:2].cpu().numpy(), out_lin[1][:2].cpu().numpy()
+        t0 = time.perf_counter()
+        nq = 0
+        for i in range(2):
+            ref_i, ref_d = oracle.linear_scan(A[i], codes_h, R)
+            nq += 1
+            if n_s == N:
+                assert np.array_equal(ref_i, got_i[i]) and np.array_equal(ref_d, got_d[i]), "GPU result differs from the oracle"
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(nq * n_s / dt, 1), "unit": "codes/s", "cores": 1, "kind": "oracle",
+               "sample": f"Alg. 1 linear scan of the first {n_s} codes for {nq} queries, top-{R}, single thread",
+               "ms_per_query_full_scan": round(dt / nq * 1e3 * (N / n_s), 1)}
+
+    line = {
+        "metric": "ADC codes scanned/sec (% of HBM peak) + queries/sec at top-k=100, 1 MI355X", "value": round(value, 1), "unit": "codes/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "N": N, "D": cfg.D, "M": M, "Ks": 256, "nlist": K, "Q": Q, "topk": R,
+                   "nprobe": nprobe, "subset_size": S, "L_query": L_query},
+        "queries_per_s": {
+            "whole_step": round(Q / (ms_per_step * 1e-3), 1),
+            "linear_scan": round(Q / (stage_ms[1] * 1e-3), 1),
+            "ivf_nprobe": round(Q / ((stage_ms[2] + stage_ms[3]) * 1e-3), 1) if K else None,
+            "subset_scan": round(Q / (stage_ms[4] * 1e-3), 1),
+            "query_alg3": round(Q / (stage_ms[5] * 1e-3), 1) if K else None,
+        },
+        "stage_ms": {"lut": round(stage_ms[0], 3), "linear": round(stage_ms[1], 3), "coarse": round(stage_ms[2], 3),
+                     "ivf": round(stage_ms[3], 3), "subset": round(stage_ms[4], 3), "query": round(stage_ms[5], 3)},
+        "codes_scored_per_step": scored,
+        "hbm_frac_of_peak": roofline["frac"],
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "index": {"paper_bytes": info["paper_bytes"], "device_bytes": info["device_bytes"], "setup_s": w["timings"]},
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

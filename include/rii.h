@@ -118,6 +118,12 @@ int rii_index_reconfigure(rii_index_t* index, int K, int iters, uint64_t seed);
 /* The threshold theta of Alg. 3 (default 0: always the inverted index when lists exist). */
 int rii_index_set_threshold(rii_index_t* index, int64_t theta);
 
+/* Measurement aid: while two hipEvent_t (passed as void*) are set, every rii_adc_scan_linear
+ * call (and the linear-scan branch of rii_query) records `start_event` right before and
+ * `stop_event` right after the kernel that streams the code array (Alg. 1, the loop over s),
+ * on the call's stream.  Pass NULL, NULL to switch it off.  The caller owns the events. */
+int rii_index_set_scan_events(rii_index_t* index, void* start_event, void* stop_event);
+
 /* info_out[0..7] = N, D, M, Ks, K (0 without lists), theta, bytes of the paper's data
  * structure ((N+K) M + 4 N, Sec. 4.1), device bytes actually held by the handle. */
 int rii_index_info(const rii_index_t* index, int64_t* info_out);

@@ -289,3 +289,10 @@ def rii_assign(index: Index, codes: torch.Tensor, coarse: torch.Tensor) -> torch
     _check(load_library().rii_assign(index.handle, _dp(codes, torch.uint8), i64(n), _dp(coarse, torch.uint8), K,
                                      _dp(out), _stream()), "rii_assign")
     return out
+
+
+def rii_index_set_scan_events(index: Index, start_event, stop_event):
+    """Measurement aid: raw hipEvent_t handles (ints or None) recorded around the linear-scan kernel."""
+    s = ctypes.c_void_p(start_event) if start_event else None
+    e = ctypes.c_void_p(stop_event) if stop_event else None
+    _check(load_library().rii_index_set_scan_events(index.handle, s, e), "rii_index_set_scan_events")

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <unordered_set>
 #include <string>
@@ -13,6 +14,10 @@
 #include "rii_internal.h"
 
 extern "C" int rii_internal_sym_table(const rii_index* idx, hipStream_t st);
+extern "C" int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, const uint8_t* super,
+                                          int G, const float* radius, const uint8_t* coarse_g, const int32_t* perm_g,
+                                          const int32_t* group_off, int32_t* assign_out,
+                                          unsigned long long* visited_total, hipStream_t st);
 extern "C" int rii_internal_gather_rows(const uint8_t* codes, const int32_t* list_ids, int64_t N, int M,
                                         uint8_t* out, hipStream_t st);
 
@@ -64,22 +69,126 @@ int install_lists(rii_index* idx, const uint8_t* coarse, int K, const std::vecto
   return RII_OK;
 }
 
-// a(n) for rows [first, first+n) of the stored codes under the host coarse centres `coarse`.
-int assign_stored(rii_index* idx, int64_t first, int64_t n, const uint8_t* coarse, int K, int32_t* assign_host) {
-  if (n == 0) return RII_OK;
-  uint8_t* d_coarse = nullptr;
-  int32_t* d_out = nullptr;
-  RII_HIP(hipMalloc(&d_coarse, (size_t)K * idx->M));
-  if (hipMalloc(&d_out, (size_t)n * 4) != hipSuccess) {
-    (void)hipGetLastError();
-    (void)hipFree(d_coarse);
-    return RII_ERR_OOM;
+// Grouping of the coarse centres used to prune the search for a(n) when K is large.
+struct CentreGroups {
+  int G = 0;
+  uint8_t* d_super = nullptr;    // [G][M]
+  float* d_radius = nullptr;     // [G]
+  uint8_t* d_coarse_g = nullptr; // [K][M] centres, group after group
+  int32_t* d_perm_g = nullptr;   // [K] original centre number of each row of d_coarse_g
+  int32_t* d_group_off = nullptr;  // [G+1]
+  ~CentreGroups() {
+    free_dev(d_super); free_dev(d_radius); free_dev(d_coarse_g); free_dev(d_perm_g); free_dev(d_group_off);
   }
+};
+
+constexpr int kPruneMinK = 1024;
+
+// Cluster the K coarse codes into G groups in code space (three rounds of the same clustering
+// reconfigure uses) and record each group's radius under d_S.
+int make_groups(rii_index* idx, const uint8_t* coarse, int K, CentreGroups& g) {
+  const int M = idx->M;
+  int G = K / 8;
+  if (G < 64) G = 64;
+  if (G > 2048) G = 2048;
+  if (G > K) G = K;
+  g.G = G;
+  int rc = rii_internal_sym_table(idx, nullptr);
+  if (rc) return rc;
+  std::vector<float> sym((size_t)M * 256 * 256);
+  RII_HIP(hipDeviceSynchronize());
+  RII_HIP(hipMemcpy(sym.data(), idx->d_sym, sym.size() * 4, hipMemcpyDeviceToHost));
+  // initial super-centres: the first G distinct coarse codes in a fixed pseudo-random order
+  std::vector<int> order(K);
+  for (int k = 0; k < K; ++k) order[k] = k;
+  std::sort(order.begin(), order.end(), [&](int a, int b) {
+    uint64_t ha = rii_host::mix64(0x5eedULL + (uint64_t)a), hb = rii_host::mix64(0x5eedULL + (uint64_t)b);
+    return ha != hb ? ha < hb : a < b;
+  });
+  std::vector<uint8_t> super((size_t)G * M);
+  {
+    std::unordered_set<std::string> seen;
+    int got = 0;
+    for (int i = 0; i < K && got < G; ++i) {
+      std::string key(reinterpret_cast<const char*>(coarse + (size_t)order[i] * M), M);
+      if (seen.insert(key).second) std::memcpy(&super[(size_t)got++ * M], key.data(), M);
+    }
+    for (int i = 0; got < G; ++i, ++got) std::memcpy(&super[(size_t)got * M], coarse + (size_t)order[i % K] * M, M);
+  }
+  uint8_t* d_coarse = nullptr;
+  int32_t* d_ga = nullptr;
+  RII_HIP(hipMalloc(&d_coarse, (size_t)K * M));
+  RII_HIP(hipMalloc(&d_ga, (size_t)K * 4));
+  RII_HIP(hipMalloc(&g.d_super, (size_t)G * M));
+  RII_HIP(hipMemcpy(d_coarse, coarse, (size_t)K * M, hipMemcpyHostToDevice));
+  std::vector<int32_t> ga(K);
+  for (int it = 0; it < 4; ++it) {
+    RII_HIP(hipMemcpy(g.d_super, super.data(), super.size(), hipMemcpyHostToDevice));
+    rc = rii_assign(idx, d_coarse, K, g.d_super, G, d_ga, nullptr);
+    if (rc) break;
+    RII_HIP(hipMemcpy(ga.data(), d_ga, (size_t)K * 4, hipMemcpyDeviceToHost));
+    if (it < 3) rii_host::update_centres(coarse, K, ga.data(), sym.data(), M, G, super.data());
+  }
+  (void)hipFree(d_coarse);
+  (void)hipFree(d_ga);
+  if (rc) return rc;
+  std::vector<float> radius(G, 0.f);
+  for (int k = 0; k < K; ++k) {
+    double d = 0;
+    for (int m = 0; m < M; ++m)
+      d += sym[((size_t)m * 256 + coarse[(size_t)k * M + m]) * 256 + super[(size_t)ga[k] * M + m]];
+    float r = (float)(std::sqrt(d) * 1.000001);
+    if (r > radius[ga[k]]) radius[ga[k]] = r;
+  }
+  std::vector<int64_t> off64;
+  std::vector<int32_t> perm;
+  rc = rii_host::build_csr(ga.data(), K, G, off64, perm);
+  if (rc) return rc;
+  std::vector<int32_t> off(off64.begin(), off64.end());
+  std::vector<uint8_t> coarse_g((size_t)K * M);
+  for (int p = 0; p < K; ++p) std::memcpy(&coarse_g[(size_t)p * M], coarse + (size_t)perm[p] * M, M);
+  RII_HIP(hipMalloc(&g.d_radius, (size_t)G * 4));
+  RII_HIP(hipMalloc(&g.d_coarse_g, (size_t)K * M));
+  RII_HIP(hipMalloc(&g.d_perm_g, (size_t)K * 4));
+  RII_HIP(hipMalloc(&g.d_group_off, (size_t)(G + 1) * 4));
+  RII_HIP(hipMemcpy(g.d_radius, radius.data(), (size_t)G * 4, hipMemcpyHostToDevice));
+  RII_HIP(hipMemcpy(g.d_coarse_g, coarse_g.data(), coarse_g.size(), hipMemcpyHostToDevice));
+  RII_HIP(hipMemcpy(g.d_perm_g, perm.data(), (size_t)K * 4, hipMemcpyHostToDevice));
+  RII_HIP(hipMemcpy(g.d_group_off, off.data(), (size_t)(G + 1) * 4, hipMemcpyHostToDevice));
+  return RII_OK;
+}
+
+// a(n) for n device-resident codes `rows` under the host coarse centres `coarse`; the result
+// stays on the device (d_out, n entries).  Brute force for small K, pruned search
+// (same result) for large K.
+int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, const uint8_t* coarse, int K, int32_t* d_out) {
+  if (n == 0) return RII_OK;
+  if (K >= kPruneMinK) {
+    CentreGroups g;
+    int rc = make_groups(idx, coarse, K, g);
+    if (rc) return rc;
+    rc = rii_internal_assign_pruned(idx, rows, n, g.d_super, g.G, g.d_radius, g.d_coarse_g, g.d_perm_g,
+                                    g.d_group_off, d_out, nullptr, nullptr);
+    if (rc) return rc;
+    RII_HIP(hipDeviceSynchronize());
+    return RII_OK;
+  }
+  uint8_t* d_coarse = nullptr;
+  RII_HIP(hipMalloc(&d_coarse, (size_t)K * idx->M));
   int rc = RII_OK;
   if (hipMemcpy(d_coarse, coarse, (size_t)K * idx->M, hipMemcpyHostToDevice) != hipSuccess) rc = RII_ERR_DEVICE;
-  if (!rc) rc = rii_assign(idx, idx->d_codes + first * idx->M, n, d_coarse, K, d_out, nullptr);
-  if (!rc && hipMemcpy(assign_host, d_out, (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
+  if (!rc) rc = rii_assign(idx, rows, n, d_coarse, K, d_out, nullptr);
+  if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
   (void)hipFree(d_coarse);
+  return rc;
+}
+
+int assign_stored(rii_index* idx, int64_t first, int64_t n, const uint8_t* coarse, int K, int32_t* assign_host) {
+  if (n == 0) return RII_OK;
+  int32_t* d_out = nullptr;
+  RII_HIP(hipMalloc(&d_out, (size_t)n * 4));
+  int rc = assign_rows_dev(idx, idx->d_codes + first * idx->M, n, coarse, K, d_out);
+  if (!rc && hipMemcpy(assign_host, d_out, (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
   (void)hipFree(d_out);
   return rc;
 }
@@ -124,6 +233,13 @@ void rii_index_destroy(rii_index_t* idx) {
 int rii_index_set_threshold(rii_index_t* idx, int64_t theta) {
   if (!idx) return RII_ERR_INVALID_ARG;
   idx->theta = theta;
+  return RII_OK;
+}
+
+int rii_index_set_scan_events(rii_index_t* idx, void* start_event, void* stop_event) {
+  if (!idx || ((start_event == nullptr) != (stop_event == nullptr))) return RII_ERR_INVALID_ARG;
+  idx->ev_start = start_event;
+  idx->ev_stop = stop_event;
   return RII_OK;
 }
 
@@ -276,22 +392,18 @@ int rii_index_reconfigure(rii_index_t* idx, int K, int iters, uint64_t seed) {
     RII_HIP(hipDeviceSynchronize());
     RII_HIP(hipMemcpy(sym.data(), idx->d_sym, sym.size() * 4, hipMemcpyDeviceToHost));
     uint8_t* d_sample = nullptr;
-    uint8_t* d_coarse = nullptr;
     int32_t* d_assign = nullptr;
     RII_HIP(hipMalloc(&d_sample, (size_t)ns * M));
-    RII_HIP(hipMalloc(&d_coarse, (size_t)K * M));
     RII_HIP(hipMalloc(&d_assign, (size_t)ns * 4));
     RII_HIP(hipMemcpy(d_sample, sample.data(), sample.size(), hipMemcpyHostToDevice));
     std::vector<int32_t> assign(ns);
     for (int it = 0; it < iters; ++it) {
-      RII_HIP(hipMemcpy(d_coarse, coarse.data(), coarse.size(), hipMemcpyHostToDevice));
-      int rc2 = rii_assign(idx, d_sample, ns, d_coarse, K, d_assign, nullptr);
+      int rc2 = assign_rows_dev(idx, d_sample, ns, coarse.data(), K, d_assign);
       if (rc2) return rc2;
       RII_HIP(hipMemcpy(assign.data(), d_assign, (size_t)ns * 4, hipMemcpyDeviceToHost));
       rii_host::update_centres(sample.data(), ns, assign.data(), sym.data(), M, K, coarse.data());
     }
     (void)hipFree(d_sample);
-    (void)hipFree(d_coarse);
     (void)hipFree(d_assign);
   }
   return rii_index_build_lists(idx, coarse.data(), K);

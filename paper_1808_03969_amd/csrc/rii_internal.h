@@ -31,6 +31,10 @@ struct rii_index {
   // scratch reused by the online calls (grown on demand)
   mutable void* ws = nullptr;
   mutable size_t ws_bytes = 0;
+
+  // optional measurement aid: events recorded right before / after the linear-scan kernel
+  void* ev_start = nullptr;
+  void* ev_stop = nullptr;
 };
 
 #define RII_HIP(call)                         \

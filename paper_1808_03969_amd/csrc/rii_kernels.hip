@@ -574,6 +574,97 @@ __global__ __launch_bounds__(256) void k_assign(const float* __restrict__ sym, c
   }
 }
 
+// a(n) with pruning, for large K.  The K centres are grouped around G "super-centres" (PQ codes
+// too); coarse_g holds the centres group after group, perm_g their original numbers, radius[j]
+// the largest sqrt(d_S) between a member of group j and its super-centre.  d_S is a squared
+// Euclidean distance between decoded vectors, so for every member c of group j
+//   sqrt(d_S(x, c)) >= sqrt(d_S(x, g_j)) - radius[j]      (triangle inequality).
+// A group is skipped only when this bound, shrunk by a rounding margin, still exceeds the best
+// distance already found; every centre that could attain the minimum (or tie with it) is
+// scored with the exact fp32 sum, so the result equals the brute-force arg-min, ties to lower k.
+template <int MT>
+__global__ __launch_bounds__(256) void k_assign_pruned(const float* __restrict__ sym, const uint8_t* __restrict__ codes,
+                                                       int64_t n, int Mrt, const uint8_t* __restrict__ super, int G,
+                                                       const float* __restrict__ radius,
+                                                       const uint8_t* __restrict__ coarse_g,
+                                                       const int32_t* __restrict__ perm_g,
+                                                       const int32_t* __restrict__ group_off,
+                                                       int32_t* __restrict__ assign, unsigned long long* visited_total) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : Mrt;
+  float* A = reinterpret_cast<float*>(smem);           // [M][256]
+  float* lb = A + M * 256;                             // [G] lower bound on d_S to any member of group j
+  __shared__ uint64_t s_red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned long long visited = 0;
+  for (int64_t item = blockIdx.x; item < n; item += gridDim.x) {
+    __syncthreads();
+    for (int i = tid; i < M * 256; i += blockDim.x) {
+      int m = i >> 8, z = i & 255;
+      A[i] = sym[((size_t)m * 256 + codes[item * M + m]) * 256 + z];
+    }
+    __syncthreads();
+    // distances to the super-centres, bounds, nearest super-centre
+    uint64_t near = kKeyMax;
+    for (int j = tid; j < G; j += blockDim.x) {
+      float d1 = adc_row<MT>(A, super + (size_t)j * M, M);
+      float root = __fsqrt_rn(d1) * 0.99999f - radius[j] * 1.00001f;
+      root = root > 0.f ? root : 0.f;
+      lb[j] = root * root * 0.99999f;
+      uint64_t key = make_key(d1, j);
+      if (key < near) near = key;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      uint64_t other = __shfl_xor(near, o, 64);
+      if (other < near) near = other;
+    }
+    if (lane == 0) s_red[wave] = near;
+    __syncthreads();
+    near = s_red[0];
+    for (int w = 1; w < 4; ++w) if (s_red[w] < near) near = s_red[w];
+    const int jstar = (int)(uint32_t)near;
+    __syncthreads();
+    // exact scores inside the nearest group
+    uint64_t best = kKeyMax;
+    for (int p = group_off[jstar] + tid; p < group_off[jstar + 1]; p += blockDim.x) {
+      uint64_t key = make_key(adc_row<MT>(A, coarse_g + (size_t)p * M, M), perm_g[p]);
+      if (key < best) best = key;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      uint64_t other = __shfl_xor(best, o, 64);
+      if (other < best) best = other;
+    }
+    if (lane == 0) s_red[wave] = best;
+    __syncthreads();
+    best = s_red[0];
+    for (int w = 1; w < 4; ++w) if (s_red[w] < best) best = s_red[w];
+    __syncthreads();
+    // every other group whose bound does not exclude it (an empty nearest group leaves best = max: all are visited)
+    for (int j = tid; j < G; j += blockDim.x) {
+      if (j == jstar) continue;
+      float bd = best == kKeyMax ? __uint_as_float(0x7F800000u) : float_of_ord((uint32_t)(best >> 32)) * 1.00001f;
+      if (lb[j] > bd) continue;
+      for (int p = group_off[j]; p < group_off[j + 1]; ++p) {
+        uint64_t key = make_key(adc_row<MT>(A, coarse_g + (size_t)p * M, M), perm_g[p]);
+        if (key < best) best = key;
+        ++visited;
+      }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      uint64_t other = __shfl_xor(best, o, 64);
+      if (other < best) best = other;
+    }
+    if (lane == 0) s_red[wave] = best;
+    __syncthreads();
+    if (tid == 0) {
+      uint64_t b = s_red[0];
+      for (int w = 1; w < 4; ++w) if (s_red[w] < b) b = s_red[w];
+      assign[item] = (int32_t)(uint32_t)b;
+    }
+  }
+  if (visited_total && visited) atomicAdd(visited_total, visited);
+}
+
 // codes_list[p] = codes[list_ids[p]]
 __global__ void k_gather_rows(const uint8_t* __restrict__ codes, const int32_t* __restrict__ list_ids, int64_t N,
                               int M4, uint32_t* __restrict__ out) {
@@ -658,8 +749,11 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   dim3 grid((unsigned)nchunks, (unsigned)Q);
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   if (mode == kLinear) {
+    const bool timed = idx->ev_start && idx->ev_stop && codes == idx->d_codes;
+    if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
     DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kLinear>, lds); if (rc) return rc;
                     k_scan<MT, kLinear><<<grid, kScanThreads, lds, st>>>(a); });
+    if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_stop), st));
   } else {
     DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kSubset>, lds); if (rc) return rc;
                     k_scan<MT, kSubset><<<grid, kScanThreads, lds, st>>>(a); });
@@ -919,6 +1013,25 @@ int rii_assign(const rii_index_t* idx, const uint8_t* codes, int64_t n, const ui
   int blocks = (int)std::min<int64_t>(n, 256 * 16);
   DISPATCH_M(M, { int rc2 = set_lds(k_assign<MT>, lds); if (rc2) return rc2;
                   k_assign<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, M, coarse, K, assign_out); });
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+// a(n) with pruning (see k_assign_pruned); all pointers device.  visited_total may be NULL.
+int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, const uint8_t* super, int G,
+                               const float* radius, const uint8_t* coarse_g, const int32_t* perm_g,
+                               const int32_t* group_off, int32_t* assign_out, unsigned long long* visited_total,
+                               hipStream_t st) {
+  if (n == 0) return RII_OK;
+  int rc = rii_internal_sym_table(idx, st);
+  if (rc) return rc;
+  const int M = idx->M;
+  const size_t lds = (size_t)M * 1024 + (size_t)G * 4;
+  if (lds > 150 * 1024) return RII_ERR_UNSUPPORTED;
+  int blocks = (int)std::min<int64_t>(n, 256 * 32);
+  DISPATCH_M(M, { int rc2 = set_lds(k_assign_pruned<MT>, lds); if (rc2) return rc2;
+                  k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, M, super, G, radius, coarse_g,
+                                                               perm_g, group_off, assign_out, visited_total); });
   RII_HIP(hipGetLastError());
   return RII_OK;
 }

@@ -158,8 +158,11 @@ def subset_batch(seed: int, N: int, sizes, device="cpu"):
     """Target identifiers for a batch of queries in CSR form.
 
     ``sizes[i]`` is |S| of query i.  Returns (target_ids int32 [sum sizes], offsets int64 [Q+1])."""
-    parts = [sorted_subset(seed, i, N, int(s), device) for i, s in enumerate(sizes)]
-    off = torch.zeros(len(parts) + 1, dtype=torch.int64)
-    off[1:] = torch.cumsum(torch.tensor([p.numel() for p in parts], dtype=torch.int64), 0)
-    ids = torch.cat(parts) if parts else torch.zeros(0, dtype=torch.int32, device=device)
+    sizes = [int(s) for s in sizes]
+    off = torch.zeros(len(sizes) + 1, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.tensor(sizes, dtype=torch.int64), 0)
+    ids = torch.empty(int(off[-1]), dtype=torch.int32, device=device)
+    for i, s in enumerate(sizes):
+        if s:
+            ids[int(off[i]):int(off[i + 1])] = sorted_subset(seed, i, N, s, device)
     return ids, off.to(device)

@@ -344,3 +344,22 @@ def test_determinism(rii, idx32):
     b = rii.rii_adc_scan_linear(d["index"], lut, 100)
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_pruned_assignment_equals_brute_force(rii, oracle_lib):
+    """K >= 1024 takes the grouped, bound-pruned search for a(n); the lists must be the ones
+    brute force gives, on clustered data (pruning active) and on unclustered data (little pruning)."""
+    for kind, seed in (("mixture", 21), ("gaussian", 22)):
+        d = make_index(rii, oracle_lib, N=30000, D=96, M=16, K=0, kind=kind, seed=seed, Q=2)
+        coarse = d["codes"][t2n(synth.sample_rows(9, 30000, 1500))].copy()
+        coarse[7] = coarse[3]  # a duplicated centre: ties must go to the lower number
+        d["index"].build_lists(coarse)
+        _, off, lids, a = d["index"].get_lists()
+        T = oracle_lib.sym_table(d["cb"])
+        a_ref = oracle_lib.assign(T, d["codes"], coarse)
+        assert np.array_equal(a, a_ref)
+        brute = rii.rii_assign(d["index"], torch.from_numpy(d["codes"]).cuda(), torch.from_numpy(coarse).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(t2n(brute), a_ref)
+        off_ref, lids_ref = oracle_lib.build_lists(a_ref, 1500)
+        assert np.array_equal(off, off_ref) and np.array_equal(lids, lids_ref)
