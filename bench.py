@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--subset", type=int, default=1_000_000, help="|S| of the subset scan")
     ap.add_argument("--nprobe", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain streaming kernel of known size (1 GiB read + 1 GiB written) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (see DESIGN.md, 'More than one "
@@ -164,6 +167,14 @@ def main():
                               "frac": round(N * M / (single_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                               "codes_per_s": round(N / (single_ms * 1e-3), 1)},
     }
+
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)  # elementwise kernel: reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:

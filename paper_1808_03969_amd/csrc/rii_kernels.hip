@@ -23,8 +23,24 @@
 namespace {
 
 constexpr int kSelCap = 2048;          // keys held per block between compactions (2 * RII_MAX_TOPK)
-constexpr int kScanThreads = 1024;
-constexpr int kRowsPerLane = 4;        // rows scored per lane between two block barriers
+#ifndef RII_SCAN_THREADS
+#define RII_SCAN_THREADS 1024
+#endif
+#ifndef RII_ROWS_PER_LANE
+#define RII_ROWS_PER_LANE 4
+#endif
+#ifndef RII_WANT_BLOCKS
+#define RII_WANT_BLOCKS 2048
+#endif
+#ifndef RII_TILE_STRIDED
+#define RII_TILE_STRIDED 0
+#endif
+#ifndef RII_TAU_EVERY
+#define RII_TAU_EVERY 1
+#endif
+constexpr int kScanThreads = RII_SCAN_THREADS;
+constexpr int kRowsPerLane = RII_ROWS_PER_LANE;  // rows scored per lane per tile
+constexpr int kPrepassBlocks = 64;               // blocks (tiles) of the bound-seeding pass, per query
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kOrdMax = 0xFFFFFFFFu;
 
@@ -51,9 +67,11 @@ __device__ __forceinline__ int next_pow2(int v) {
 }
 
 // Ascending bitonic sort of keys[0..n2), n2 a power of two.  Block-wide; ends with a barrier.
-__device__ void block_bitonic_sort(uint64_t* keys, int n2) {
+// With first_size > 2 the stages below first_size are skipped: the caller guarantees that the
+// runs of first_size/2 keys are already sorted, alternately ascending and descending.
+__device__ void block_bitonic_sort(uint64_t* keys, int n2, int first_size = 2) {
   const int tid = threadIdx.x, nthr = blockDim.x;
-  for (int size = 2; size <= n2; size <<= 1) {
+  for (int size = first_size; size <= n2; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
       for (int t = tid; t < (n2 >> 1); t += nthr) {
         int i = 2 * t - (t & (stride - 1));
@@ -180,10 +198,18 @@ struct ScanArgs {
   const int64_t* target_offsets; // subset mode, [Q+1]
   int64_t chunk_rows;            // rows (or targets) per block
   int k;
-  uint64_t* partial;             // [Q][gridDim.x][k]
+  uint64_t* partial;             // [Q][cand_cap] candidate keys appended by the blocks
+  uint32_t* cand_cnt;            // [Q] number of candidates appended
+  int64_t cand_cap;              // gridDim.x * k
   uint32_t* tau_g;               // [Q] shared distance bound per query
   const int* qmode;              // optional [Q]; block runs only when qmode[q] == want_mode
   int want_mode;
+  uint32_t* done_cnt;            // [Q] blocks finished (the last one selects the result)
+  int32_t* ids;                  // result [Q][out_stride] (written by k_scan_w only)
+  float* dist;
+  int out_stride;
+  uint32_t* minima;              // bound-seeding pass: [Q][gridDim.x * waves] smallest distance image per wave
+  uint32_t* counter;             // bound-seeding pass: [Q] blocks finished
 };
 
 enum { kLinear = 0, kSubset = 1 };
@@ -199,7 +225,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(ScanArgs a) {
 
   const int tid = threadIdx.x;
   const int64_t q = blockIdx.y;
-  uint64_t* part = a.partial + (q * gridDim.x + blockIdx.x) * a.k;
+  uint64_t* cand = a.partial + q * a.cand_cap;
   if (a.qmode && a.qmode[q] != a.want_mode) return;
 
   int64_t nrows;
@@ -213,10 +239,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(ScanArgs a) {
   }
   const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
   const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
-  if (r0 >= r1) {
-    for (int i = tid; i < a.k; i += blockDim.x) part[i] = kKeyMax;
-    return;
-  }
+  if (r0 >= r1) return;
 
   const float* lut = a.lut + q * M * 256;
   for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
@@ -251,14 +274,395 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(ScanArgs a) {
   sel_compact(keys, &s_cnt, &s_tau, a.k);
   if (tid == 0) atomicMin(a.tau_g + q, s_tau);
   const int c = s_cnt;
-  for (int i = tid; i < a.k; i += blockDim.x) part[i] = i < c ? keys[i] : kKeyMax;
+  __shared__ uint32_t s_base;
+  if (tid == 0) s_base = c ? atomicAdd(a.cand_cnt + q, (uint32_t)c) : 0u;
+  __syncthreads();
+  for (int i = tid; i < c; i += blockDim.x) cand[s_base + i] = keys[i];
+}
+
+__device__ __forceinline__ void write_result(const uint64_t* keys, int c, int k, int32_t* ids, float* dist);
+
+// ------------------------------------------------------------------ scan with per-wave selection
+// For topk <= kWaveK every wavefront keeps its own candidate buffer (kWaveCap keys in LDS) and
+// its own distance bound, so the loop over the rows has no block barrier: a wave that has no
+// candidate in a tile (the common case once its bound has tightened) just goes on streaming.
+// A full buffer is compacted by the wave alone (bitonic sort of its kWaveCap keys).  At the end
+// the waves' sorted buffers are merged by the block.
+constexpr int kWaveK = 128;
+constexpr int kWaveCap = 256;
+
+// Cross-block hand-over without cache-wide fences: the data is written with agent-scope
+// atomic stores (which go through to the coherence point), the writer waits for its own stores
+// to complete, and only then takes its ticket; the reader uses agent-scope atomic loads.
+__device__ __forceinline__ void wait_own_memory_ops() { __builtin_amdgcn_s_waitcnt(0); }
+
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// Ascending bitonic sort of buf[0..n2) by one wavefront (n2 a power of two, at most kWaveCap).
+__device__ __forceinline__ void wave_bitonic_sort(uint64_t* buf, int n2, int lane) {
+  for (int size = 2; size <= n2; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = lane; t < (n2 >> 1); t += 64) {
+        int i = 2 * t - (t & (stride - 1));
+        int j = i + stride;
+        bool up = ((i & size) == 0);
+        uint64_t a = buf[i], b = buf[j];
+        if ((a > b) == up) {
+          buf[i] = b;
+          buf[j] = a;
+        }
+      }
+      wave_sync();
+    }
+  }
+}
+
+// Sort the wave's buffer, keep its k smallest keys, tighten the wave's bound.
+__device__ __forceinline__ void wave_compact(uint64_t* buf, int& cnt, uint32_t& tau, int k, int lane) {
+  int n2 = next_pow2(cnt);
+  for (int i = cnt + lane; i < n2; i += 64) buf[i] = kKeyMax;
+  wave_sync();
+  wave_bitonic_sort(buf, n2, lane);
+  if (cnt >= k) {
+    cnt = k;
+    uint32_t t = (uint32_t)(buf[k - 1] >> 32);
+    if (t < tau) tau = t;
+  }
+}
+
+template <int R>
+__device__ __forceinline__ void wave_offer(uint64_t* buf, int& cnt, uint32_t& tau, int k, const uint64_t (&key)[R],
+                                           uint32_t pend, int lane) {
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    bool p = ((pend >> r) & 1u) && (uint32_t)(key[r] >> 32) <= tau;
+    unsigned long long m;
+    while ((m = __ballot(p)) != 0ull) {
+      const int room = kWaveCap - cnt;
+      const int rank = __popcll(m & ((1ull << lane) - 1ull));
+      const int n = __popcll(m);
+      if (p && rank < room) {
+        buf[cnt + rank] = key[r];
+        p = false;
+      }
+      cnt += n < room ? n : room;
+      if (cnt == kWaveCap) {
+        wave_sync();
+        wave_compact(buf, cnt, tau, k, lane);
+        p = p && (uint32_t)(key[r] >> 32) <= tau;
+      }
+    }
+  }
+}
+
+// Bound-seeding pass.  Block b of query q scores the b-th tile of the query's rows; every wave
+// records the smallest distance among its rows.  The k-th smallest of these minima belongs to
+// k different rows, so it bounds the k-th smallest distance of the whole scan from above.  The
+// block that finishes last selects it (one wave, bit-by-bit search) and stores it in tau_g.
+template <int MT, int MODE>
+__global__ __launch_bounds__(kScanThreads) void k_tau0(ScanArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : a.M;
+  float* A = reinterpret_cast<float*>(smem);
+  __shared__ int s_last;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  const int64_t q = blockIdx.y;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
+  int64_t nrows;
+  const int32_t* tids = nullptr;
+  if (MODE == kLinear) {
+    nrows = a.N;
+  } else {
+    int64_t o0 = a.target_offsets[q];
+    nrows = a.target_offsets[q + 1] - o0;
+    tids = a.target_ids + o0;
+  }
+  const int G = gridDim.x * nwaves;
+  uint32_t* minima = a.minima + q * G;
+  const int64_t r0 = (int64_t)blockIdx.x * blockDim.x * kRowsPerLane;
+  uint32_t best = kOrdMax;
+  if (r0 < nrows) {  // block-uniform
+    const float* lut = a.lut + q * M * 256;
+    for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRowsPerLane; ++r) {
+      int64_t i = r0 + (int64_t)r * blockDim.x + tid;
+      if (i < nrows) {
+        int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
+        uint32_t o = ord_of(adc_row<MT>(A, a.codes + (int64_t)id * M, M));
+        if (o < best) best = o;
+      }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      uint32_t other = __shfl_xor(best, o, 64);
+      if (other < best) best = other;
+    }
+  }
+  if (lane == 0) __hip_atomic_store(minima + blockIdx.x * nwaves + wave, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  wait_own_memory_ops();
+  __syncthreads();
+  if (tid == 0) s_last = atomicAdd(a.counter + q, 1u) == gridDim.x - 1;
+  __syncthreads();
+  if (!s_last || wave != 0) return;
+  // k-th smallest of the G minima, most significant bit first: bit b of the answer is 0 when at
+  // least k values lie below (answer | 1 << b).  Each lane keeps its share of the values in registers.
+  const int k = a.k;
+  if (G < k) return;
+  constexpr int kPerLane = kPrepassBlocks * (kScanThreads / 64) / 64;
+  uint32_t v[kPerLane];
+#pragma unroll
+  for (int j = 0; j < kPerLane; ++j) {
+    int i = lane + 64 * j;
+    v[j] = i < G ? __hip_atomic_load(minima + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kOrdMax;
+  }
+  uint32_t ans = 0;
+  for (int b = 31; b >= 0; --b) {
+    const uint32_t trial = ans | (1u << b);
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) c += v[j] < trial;
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+    if (c < k) ans = trial;
+  }
+  if (lane == 0 && ans != kOrdMax) atomicMin(a.tau_g + q, ans);
+}
+
+// The waves of a block hold cnt keys each in their buffers.  Leaves the block's k smallest keys
+// (of those not above `bound`), sorted ascending, at (*out)[0..c) and returns c.  Block-wide;
+// ends with a barrier.  wbuf = [nwaves][kWaveCap] wave buffers followed by one more kWaveCap keys.
+__device__ int block_collect(uint64_t* wbuf, int nwaves, int cnt, uint32_t tau, uint32_t bound, int k,
+                             uint64_t** out, int* s_total, int* s_off) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
+  uint64_t* small = wbuf + (size_t)nwaves * kWaveCap;
+  if (tid == 0) {
+    *s_total = 0;
+    *s_off = 0;
+  }
+  wave_sync();
+  // Fast path: when only a few keys can still matter, gather them and let one wave sort them.
+  int nsurv = 0;
+  for (int i0 = 0; i0 < cnt; i0 += 64) {
+    int i = i0 + lane;
+    bool keep = i < cnt && (uint32_t)(buf[i] >> 32) <= bound;
+    nsurv += __popcll(__ballot(keep));
+  }
+  __syncthreads();
+  if (lane == 0 && nsurv) atomicAdd(s_total, nsurv);
+  __syncthreads();
+  const int total = *s_total;
+  if (total <= kWaveCap) {
+    int base = 0;
+    if (lane == 0 && nsurv) base = atomicAdd(s_off, nsurv);
+    base = __shfl(base, 0, 64);
+    for (int i0 = 0; i0 < cnt; i0 += 64) {
+      int i = i0 + lane;
+      bool keep = i < cnt && (uint32_t)(buf[i] >> 32) <= bound;
+      unsigned long long m = __ballot(keep);
+      if (keep) small[base + __popcll(m & ((1ull << lane) - 1ull))] = buf[i];
+      base += __popcll(m);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      int c = total;
+      uint32_t t = kOrdMax;
+      wave_compact(small, c, t, k, lane);
+    }
+    __syncthreads();
+    *out = small;
+    return total < k ? total : k;
+  }
+  // General path: every wave sorts what it holds and keeps at most k keys; the runs (kp keys
+  // each, alternately ascending / descending, padded with the largest key) are packed at the
+  // start of the buffer area and merged by the last stages of a block-wide bitonic sort.
+  wave_compact(buf, cnt, tau, k, lane);
+  if (cnt > k) cnt = k;
+  const int kp = next_pow2(k);
+  uint64_t mine[kWaveK / 64];
+#pragma unroll
+  for (int j = 0; j < kWaveK / 64; ++j) {
+    int i = lane + 64 * j;
+    mine[j] = (i < cnt) ? buf[i] : kKeyMax;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kWaveK / 64; ++j) {
+    int i = lane + 64 * j;
+    if (i < kp) wbuf[(size_t)wave * kp + ((wave & 1) ? (kp - 1 - i) : i)] = mine[j];
+  }
+  __syncthreads();
+  block_bitonic_sort(wbuf, nwaves * kp, 2 * kp);
+  // the first c <= k keys are real candidates (the padding sorts last)
+  if (tid == 0) *s_total = 0;
+  __syncthreads();
+  if (tid < k && wbuf[tid] != kKeyMax && (tid == k - 1 || wbuf[tid + 1] == kKeyMax)) *s_total = tid + 1;
+  __syncthreads();
+  *out = wbuf;
+  return *s_total;
+}
+
+template <int MT, int MODE>
+__global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : a.M;
+  float* A = reinterpret_cast<float*>(smem);
+  uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + (size_t)M * 1024);  // [waves + 1][kWaveCap]
+  __shared__ int s_total, s_off, s_last;
+  __shared__ uint32_t s_tg;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  const int64_t q = blockIdx.y;
+  uint64_t* cand = a.partial + q * a.cand_cap;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
+
+  int64_t nrows;
+  const int32_t* tids = nullptr;
+  if (MODE == kLinear) {
+    nrows = a.N;
+  } else {
+    int64_t o0 = a.target_offsets[q];
+    nrows = a.target_offsets[q + 1] - o0;
+    tids = a.target_ids + o0;
+  }
+  const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
+  const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
+  uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
+  const int k = a.k;
+
+  if (r0 < r1) {  // block-uniform
+    const float* lut = a.lut + q * M * 256;
+    for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
+    __syncthreads();
+    int cnt = 0;
+    uint32_t tau = kOrdMax;
+    const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
+    // The query's shared bound is re-read once per tile by the block's first wave only and
+    // passed on through LDS (a plain word, read without synchronisation: a stale value is
+    // still a valid bound); thousands of waves polling one address would serialise on it.
+    uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    for (int64_t tile = r0; tile < r1; tile += tile_step) {
+      uint64_t key[kRowsPerLane];
+      uint32_t pend = 0;
+      uint32_t fresh = kOrdMax;
+      if (wave == 0) fresh = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t bound = tg < tau ? tg : tau;
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) {
+        // a wave owns 64 consecutive rows of each of the tile's kRowsPerLane slices
+        int64_t i = tile + (int64_t)r * blockDim.x + tid;
+        key[r] = kKeyMax;
+        if (i < r1) {
+          int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
+          float d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
+          key[r] = make_key(d, id);
+          if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
+        }
+      }
+      if (__ballot(pend != 0) != 0ull) {
+        const uint32_t before = tau;
+        wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
+        if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
+      }
+      if (tid == 0) __hip_atomic_store(&s_tg, fresh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      tg = __hip_atomic_load(&s_tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the block's own k best go to the query's candidate list
+    const uint32_t bound = tg < tau ? tg : tau;
+    uint64_t* best;
+    const int c = block_collect(wbuf, nwaves, cnt, tau, bound, k, &best, &s_total, &s_off);
+    if (tid == 0) {
+      s_off = c ? (int)atomicAdd(a.cand_cnt + q, (uint32_t)c) : 0;
+      if (c >= k) atomicMin(a.tau_g + q, (uint32_t)(best[k - 1] >> 32));
+    }
+    __syncthreads();
+    for (int i = tid; i < c; i += blockDim.x)
+      __hip_atomic_store(cand + (uint32_t)s_off + i, best[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // ---- the block that finishes last selects the query's result from the candidate list
+  wait_own_memory_ops();
+  __syncthreads();
+  if (tid == 0) s_last = atomicAdd(a.done_cnt + q, 1u) == gridDim.x - 1;
+  __syncthreads();
+  if (!s_last) return;
+#ifdef RII_DEBUG_SKIP_FINAL
+  return;
+#endif
+  const int64_t n = __hip_atomic_load(a.cand_cnt + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  constexpr int kBatch = 8;  // keys per lane in flight: the loads bypass the caches, so overlap them
+  // Pass A: every thread takes the smallest distance image of its strided share of the
+  // candidates; the k-th smallest of these per-thread minima (k different candidates) bounds
+  // the k-th smallest candidate, and about k candidates lie below it.
+  uint32_t tau = kOrdMax;
+  if (n > kWaveCap) {
+    uint32_t mine = kOrdMax;
+    for (int64_t i0 = 0; i0 < n; i0 += (int64_t)blockDim.x * kBatch) {
+      uint64_t key[kBatch];
+#pragma unroll
+      for (int r = 0; r < kBatch; ++r) {
+        const int64_t i = i0 + (int64_t)r * blockDim.x + tid;
+        key[r] = i < n ? __hip_atomic_load(cand + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kKeyMax;
+      }
+#pragma unroll
+      for (int r = 0; r < kBatch; ++r) {
+        uint32_t o = (uint32_t)(key[r] >> 32);
+        if (o < mine) mine = o;
+      }
+    }
+    uint32_t* s_min = reinterpret_cast<uint32_t*>(wbuf);  // [blockDim.x]
+    s_min[tid] = mine;
+    __syncthreads();
+    if ((int)blockDim.x >= k) {  // every wave finds the same value: no broadcast needed
+      uint32_t v[kScanThreads / 64];
+#pragma unroll
+      for (int j = 0; j < kScanThreads / 64; ++j) v[j] = s_min[lane + 64 * j];
+      uint32_t ans = 0;
+      for (int b = 31; b >= 0; --b) {
+        const uint32_t trial = ans | (1u << b);
+        int c = 0;
+#pragma unroll
+        for (int j = 0; j < kScanThreads / 64; ++j) c += v[j] < trial;
+        for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+        if (c < k) ans = trial;
+      }
+      tau = ans;
+    }
+    __syncthreads();
+  }
+  // Pass B: keep what is not above the bound (per-wave buffers as in the scan), then merge.
+  int cnt = 0;
+  for (int64_t i0 = (int64_t)wave * 64 * kBatch; i0 < n; i0 += (int64_t)nwaves * 64 * kBatch) {
+    uint64_t key[kBatch];
+    uint32_t pend = 0;
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r) {
+      const int64_t i = i0 + r * 64 + lane;
+      key[r] = i < n ? __hip_atomic_load(cand + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kKeyMax;
+    }
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r)
+      if (key[r] != kKeyMax && (uint32_t)(key[r] >> 32) <= tau) pend |= 1u << r;
+    if (__ballot(pend != 0) != 0ull) wave_offer<kBatch>(buf, cnt, tau, k, key, pend, lane);
+  }
+  uint64_t* best;
+  const int c = block_collect(wbuf, nwaves, cnt, tau, kOrdMax, k, &best, &s_total, &s_off);
+  write_result(best, c, k, a.ids + q * a.out_stride, a.dist ? a.dist + q * a.out_stride : nullptr);
 }
 
 // ------------------------------------------------------------------ PartialSort + Take
 struct SelectArgs {
   // source A: keys [Q][nkeys] (per-block partial results)
   const uint64_t* keys;
-  int64_t nkeys;
+  int64_t nkeys;               // capacity per query
+  const uint32_t* key_cnt;     // [Q] keys actually present (NULL: nkeys)
   // source B: explicit candidates in CSR segments
   const float* cand_dist;
   const int32_t* cand_ids;
@@ -299,6 +703,7 @@ __global__ __launch_bounds__(kScanThreads) void k_select(SelectArgs a) {
   int64_t n, base = 0;
   if (a.keys) {
     n = a.nkeys;
+    if (a.key_cnt && a.key_cnt[q] < n) n = a.key_cnt[q];
   } else {
     base = a.cand_offsets[q];
     n = a.cand_offsets[q + 1] - base;
@@ -461,6 +866,16 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
 }
 
 // ------------------------------------------------------------------ small utility kernels
+// tau[q] = largest bound; the three counter arrays that follow it (stride entries apart) = 0
+__global__ void k_init_scan(uint32_t* tau, int Q, int stride) {
+  int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= Q) return;
+  tau[q] = kOrdMax;
+  tau[stride + q] = 0u;
+  tau[2 * (size_t)stride + q] = 0u;
+  tau[3 * (size_t)stride + q] = 0u;
+}
+
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -716,6 +1131,21 @@ int set_lds(Kern kern, size_t bytes) {
     default: { constexpr int MT = 0; __VA_ARGS__; } break;  \
   }
 
+// Split max_rows rows per query into equal chunks (one block each): about kWantBlocks blocks
+// in total when the batch is small, never chunks shorter than kMinTiles tiles.
+constexpr int kWantBlocks = RII_WANT_BLOCKS;
+constexpr int kMinTiles = 4;
+void scan_chunks(int Q, int64_t max_rows, int64_t* nchunks_out, int64_t* chunk_rows_out) {
+  const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
+  int64_t want = (kWantBlocks + Q - 1) / Q;
+  int64_t most = std::max<int64_t>(1, (max_rows + kMinTiles * tile - 1) / (kMinTiles * tile));
+  int64_t nchunks = std::min<int64_t>(std::min(want, most), 65535);
+  int64_t chunk_rows = (max_rows + nchunks - 1) / nchunks;
+  chunk_rows = std::max<int64_t>(tile, (chunk_rows + tile - 1) / tile * tile);
+  *nchunks_out = std::max<int64_t>(1, (max_rows + chunk_rows - 1) / chunk_rows);
+  *chunk_rows_out = chunk_rows;
+}
+
 // Scan `nrows_max` rows per query (linear: the whole array) and leave per-block partial keys in
 // the workspace; then select.  Workspace layout: [tau Q u32][partial Q*nchunks*k u64].
 int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const float* lut, int Q, int mode,
@@ -723,55 +1153,81 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
                 int32_t* ids, float* dist, int out_stride, const int* qmode, int want_mode, void* ws_base,
                 hipStream_t st) {
   const int M = idx->M;
-  const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
-  // enough blocks to fill the chip several times over, but chunks of at least 16 tiles
-  int64_t want_chunks = (4096 + Q - 1) / Q;
-  int64_t max_chunks = (max_rows + 16 * tile - 1) / (16 * tile);
-  if (max_chunks < 1) max_chunks = 1;
-  int64_t nchunks = std::min(want_chunks, max_chunks);
-  if (nchunks > 65535) nchunks = 65535;
-  int64_t chunk_rows = (max_rows + nchunks - 1) / nchunks;
-  chunk_rows = (chunk_rows + tile - 1) / tile * tile;
-  if (chunk_rows < tile) chunk_rows = tile;
-  nchunks = std::max<int64_t>(1, (max_rows + chunk_rows - 1) / chunk_rows);
+  int64_t nchunks, chunk_rows;
+  scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
 
+  // workspace: [tau Q][candidate count Q][prepass counter Q][blocks done Q] u32, then
+  // [candidates], then [prepass minima]
+  // (the four arrays start 256-byte aligned so that, for a single query, the much-read bound
+  // does not share a cache line with the counters the blocks update)
   uint8_t* base = static_cast<uint8_t*>(ws_base);
+  const size_t cstride = align_up((size_t)Q * 4, 256) / 4;
   uint32_t* tau = reinterpret_cast<uint32_t*>(base);
-  uint64_t* partial = reinterpret_cast<uint64_t*>(base + align_up((size_t)Q * 4, 256));
+  uint32_t* cand_cnt = tau + cstride;
+  uint32_t* pre_counter = tau + 2 * cstride;
+  uint32_t* done_cnt = tau + 3 * cstride;
+  uint64_t* partial = reinterpret_cast<uint64_t*>(base + 4 * cstride * 4);
 
-  k_fill_u32<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, kOrdMax);
+  k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
   ScanArgs a{};
   a.codes = codes; a.N = N; a.M = M; a.lut = lut;
   a.target_ids = target_ids; a.target_offsets = target_offsets;
   a.chunk_rows = chunk_rows; a.k = topk; a.partial = partial; a.tau_g = tau;
+  a.cand_cnt = cand_cnt; a.cand_cap = nchunks * topk;
+  a.done_cnt = done_cnt; a.ids = ids; a.dist = dist; a.out_stride = out_stride;
   a.qmode = qmode; a.want_mode = want_mode;
-  const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
   dim3 grid((unsigned)nchunks, (unsigned)Q);
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
+  const bool timed = mode == kLinear && idx->ev_start && idx->ev_stop && codes == idx->d_codes;
+  if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
+  if (topk <= kWaveK) {
+    // When a query's rows are split over several blocks, a short first pass over the leading
+    // rows seeds the shared bound, so that the main pass starts with few candidates.
+    const int64_t tile_rows = (int64_t)kScanThreads * kRowsPerLane;
+    const int pre_blocks = (int)std::min<int64_t>(kPrepassBlocks, (max_rows + tile_rows - 1) / tile_rows);
+    const bool prepass = nchunks > 1;
+    ScanArgs pre = a;
+    pre.minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * nchunks * topk);
+    pre.counter = pre_counter;
+    dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
+    const size_t ldsw = (size_t)M * 1024 + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+    if (mode == kLinear) {
+      DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kLinear>, ldsw); if (rc) return rc;
+                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kLinear>, (size_t)M * 1024); if (rc2) return rc2; }
+                      if (prepass) k_tau0<MT, kLinear><<<pgrid, kScanThreads, (size_t)M * 1024, st>>>(pre);
+                      k_scan_w<MT, kLinear><<<grid, kScanThreads, ldsw, st>>>(a); });
+    } else {
+      DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kSubset>, ldsw); if (rc) return rc;
+                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kSubset>, (size_t)M * 1024); if (rc2) return rc2; }
+                      if (prepass) k_tau0<MT, kSubset><<<pgrid, kScanThreads, (size_t)M * 1024, st>>>(pre);
+                      k_scan_w<MT, kSubset><<<grid, kScanThreads, ldsw, st>>>(a); });
+    }
+  } else {
+  const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
   if (mode == kLinear) {
-    const bool timed = idx->ev_start && idx->ev_stop && codes == idx->d_codes;
-    if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
     DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kLinear>, lds); if (rc) return rc;
                     k_scan<MT, kLinear><<<grid, kScanThreads, lds, st>>>(a); });
-    if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_stop), st));
   } else {
     DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kSubset>, lds); if (rc) return rc;
                     k_scan<MT, kSubset><<<grid, kScanThreads, lds, st>>>(a); });
   }
-  SelectArgs s{};
-  s.keys = partial; s.nkeys = nchunks * topk; s.k = topk; s.out_stride = out_stride;
-  s.ids = ids; s.dist = dist; s.qmode = qmode; s.want_mode = want_mode;
-  k_select<<<Q, kScanThreads, 0, st>>>(s);
+  }
+  if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_stop), st));
+  if (topk > kWaveK) {
+    SelectArgs s{};
+    s.keys = partial; s.nkeys = nchunks * topk; s.key_cnt = cand_cnt; s.k = topk; s.out_stride = out_stride;
+    s.ids = ids; s.dist = dist; s.qmode = qmode; s.want_mode = want_mode;
+    k_select<<<Q, kScanThreads, 0, st>>>(s);
+  }
   RII_HIP(hipGetLastError());
   return RII_OK;
 }
 
 size_t scan_ws_bytes(int Q, int64_t max_rows, int topk) {
-  const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
-  int64_t want_chunks = (4096 + Q - 1) / Q;
-  int64_t max_chunks = std::max<int64_t>(1, (max_rows + 16 * tile - 1) / (16 * tile));
-  int64_t nchunks = std::min<int64_t>(std::min(want_chunks, max_chunks), 65535) + 1;
-  return align_up((size_t)Q * 4, 256) + (size_t)Q * nchunks * topk * 8 + 256;
+  int64_t nchunks, chunk_rows;
+  scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
+  return 4 * align_up((size_t)Q * 4, 256) + (size_t)Q * nchunks * topk * 8 +
+         (size_t)Q * kPrepassBlocks * (kScanThreads / 64) * 4 + 256;
 }
 
 }  // namespace

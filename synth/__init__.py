@@ -154,14 +154,59 @@ def sorted_subset(seed: int, query: int, N: int, S: int, device="cpu") -> torch.
     return uniq.to(torch.int32)
 
 
-def subset_batch(seed: int, N: int, sizes, device="cpu"):
+def _draw_count(N: int, S: int) -> int:
+    expected_dup = S * S / (2.0 * N)
+    return S + int(2 * expected_dup + 8 * math.sqrt(expected_dup + 1) + 16)
+
+
+def _sorted_subsets_equal_size(seed: int, q0: int, B: int, N: int, S: int, device) -> torch.Tensor | None:
+    """``sorted_subset`` for queries q0..q0+B-1 at once ([B][S] int32), or None if a row came up short."""
+    n_draw = _draw_count(N, S)
+    idx = torch.arange(n_draw, dtype=torch.int64, device=device)
+    key1 = torch.tensor([_seed_key(seed, 16 + 2 * (q0 + b)) for b in range(B)], dtype=torch.int64, device=device)
+    key2 = torch.tensor([_seed_key(seed, 17 + 2 * (q0 + b)) for b in range(B)], dtype=torch.int64, device=device)
+    draws = _lsr(_mix64(_mix64(idx[None, :] * _GOLD + key1[:, None])), 1) % N
+    vals = torch.sort(draws, dim=1).values
+    dup = torch.zeros_like(vals, dtype=torch.bool)
+    dup[:, 1:] = vals[:, 1:] == vals[:, :-1]
+    U = (~dup).sum(dim=1)
+    if int(U.min()) < S:
+        return None
+    big = torch.iinfo(torch.int64).max
+    drop_key = _mix64(_mix64(vals * _GOLD + key2[:, None]))
+    drop_key = torch.where(dup, torch.full_like(drop_key, big), drop_key)
+    ordered = torch.sort(drop_key, dim=1).values
+    n_drop = U - S                                  # members to drop per row: the n_drop smallest keys
+    thr = torch.where(n_drop > 0, ordered.gather(1, (n_drop - 1).clamp(min=0)[:, None]).squeeze(1),
+                      torch.full_like(n_drop, -big - 1))
+    keep = (~dup) & ((drop_key > thr[:, None]) | (n_drop == 0)[:, None])
+    if not bool((keep.sum(dim=1) == S).all()):      # a tie between 64-bit keys: practically never
+        return None
+    return vals[keep].view(B, S).to(torch.int32)
+
+
+def subset_batch(seed: int, N: int, sizes, device="cpu", batch: int = 64):
     """Target identifiers for a batch of queries in CSR form.
 
-    ``sizes[i]`` is |S| of query i.  Returns (target_ids int32 [sum sizes], offsets int64 [Q+1])."""
+    ``sizes[i]`` is |S| of query i.  Returns (target_ids int32 [sum sizes], offsets int64 [Q+1]).
+    Query i gets ``sorted_subset(seed, i, N, sizes[i])``; equal sizes are produced many queries
+    at a time with the same arithmetic."""
     sizes = [int(s) for s in sizes]
     off = torch.zeros(len(sizes) + 1, dtype=torch.int64)
     off[1:] = torch.cumsum(torch.tensor(sizes, dtype=torch.int64), 0)
     ids = torch.empty(int(off[-1]), dtype=torch.int32, device=device)
+    Q = len(sizes)
+    S = sizes[0] if sizes else 0
+    if Q > 1 and all(s == S for s in sizes) and 0 < S < N and 2 * S <= N:
+        while batch > 1 and batch * _draw_count(N, S) > (1 << 27):
+            batch //= 2
+        for q0 in range(0, Q, batch):
+            B = min(batch, Q - q0)
+            rows = _sorted_subsets_equal_size(seed, q0, B, N, S, device)
+            if rows is None:
+                rows = torch.stack([sorted_subset(seed, q0 + b, N, S, device) for b in range(B)])
+            ids[q0 * S:(q0 + B) * S] = rows.reshape(-1)
+        return ids, off.to(device)
     for i, s in enumerate(sizes):
         if s:
             ids[int(off[i]):int(off[i + 1])] = sorted_subset(seed, i, N, s, device)
