@@ -30,6 +30,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the batched linear-scan kernel, from the rocprofv3 PMC runs summarised in
+# profiles/k_scan_w_c5_hbm_traffic_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated
+# with a plain streaming kernel).  Reported only for the exact configuration it was measured on.
+MEASURED_TRAFFIC = {("c5_billion_shard", 100_000_000, 10_000): 5_667_408_747 * 2.0 * 1024 + 44_005 * 1024}
+
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
@@ -160,8 +165,9 @@ def main():
     alg_bytes = float(Q) * N * M          # M bytes per code and query pass
     achieved = alg_bytes / (scan_avg_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": f"k_scan<{M},linear>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "bound": "hbm", "kernel": f"k_scan_w<{M},linear>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC.get((cfg.name, N, Q)),
         "launch_ms": round(scan_avg_ms, 3), "algorithmic_bytes_per_launch": alg_bytes,
         "single_query_pass": {"launch_ms": round(single_ms, 4), "achieved": round(N * M / (single_ms * 1e-3) / 1e9, 1),
                               "frac": round(N * M / (single_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -146,7 +146,7 @@ def sorted_subset(seed: int, query: int, N: int, S: int, device="cpu") -> torch.
             break
         extra += n_draw  # practically never reached
     if U > S:
-        drop_key = hash64(seed, stream + 1, uniq)
+        drop_key = _lsr(hash64(seed, stream + 1, uniq), 1)  # unsigned order of the hash
         drop = torch.topk(drop_key, U - S, largest=False).indices
         keep = torch.ones(U, dtype=torch.bool, device=device)
         keep[drop] = False
@@ -166,21 +166,26 @@ def _sorted_subsets_equal_size(seed: int, q0: int, B: int, N: int, S: int, devic
     key1 = torch.tensor([_seed_key(seed, 16 + 2 * (q0 + b)) for b in range(B)], dtype=torch.int64, device=device)
     key2 = torch.tensor([_seed_key(seed, 17 + 2 * (q0 + b)) for b in range(B)], dtype=torch.int64, device=device)
     draws = _lsr(_mix64(_mix64(idx[None, :] * _GOLD + key1[:, None])), 1) % N
-    vals = torch.sort(draws, dim=1).values
+    # one flat sort per step (row number in the high bits) instead of one sort per row
+    row = torch.arange(B, dtype=torch.int64, device=device)[:, None]
+    vals = (torch.sort(((row << 32) | draws).view(-1)).values & 0xFFFFFFFF).view(B, n_draw)
     dup = torch.zeros_like(vals, dtype=torch.bool)
     dup[:, 1:] = vals[:, 1:] == vals[:, :-1]
     U = (~dup).sum(dim=1)
     if int(U.min()) < S:
         return None
-    big = torch.iinfo(torch.int64).max
-    drop_key = _mix64(_mix64(vals * _GOLD + key2[:, None]))
+    # the U-S members with the smallest hash are dropped; the comparison uses the top 36 bits
+    # of the hash, which selects the same members unless two of them tie exactly at the cut
+    # (then the row count check below fails and the caller falls back to sorted_subset)
+    big = (1 << 36) - 1
+    drop_key = _lsr(_mix64(_mix64(vals * _GOLD + key2[:, None])), 28)
     drop_key = torch.where(dup, torch.full_like(drop_key, big), drop_key)
-    ordered = torch.sort(drop_key, dim=1).values
+    ordered = (torch.sort(((row << 36) | drop_key).view(-1)).values & big).view(B, n_draw)
     n_drop = U - S                                  # members to drop per row: the n_drop smallest keys
     thr = torch.where(n_drop > 0, ordered.gather(1, (n_drop - 1).clamp(min=0)[:, None]).squeeze(1),
-                      torch.full_like(n_drop, -big - 1))
-    keep = (~dup) & ((drop_key > thr[:, None]) | (n_drop == 0)[:, None])
-    if not bool((keep.sum(dim=1) == S).all()):      # a tie between 64-bit keys: practically never
+                      torch.full_like(n_drop, -1))
+    keep = (~dup) & (drop_key > thr[:, None])
+    if not bool((keep.sum(dim=1) == S).all()):
         return None
     return vals[keep].view(B, S).to(torch.int32)
 
