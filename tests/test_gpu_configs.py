@@ -1,0 +1,260 @@
+"""The five benchmark configurations at their full sizes, in the launch shapes bench.py times.
+
+At these sizes the oracle cannot score every (query, code) pair, so each configuration is checked on
+three levels:
+  * full oracle runs (Alg. 1 / Alg. 2 / Alg. 3 on the very same code array, copied to the host) for
+    a seeded sample of queries: identifiers bit-exact, distances bit-identical (bar: 1e-5 relative);
+  * certificates for *every* query of the batch: each returned (id, distance) pair is recomputed
+    by the oracle's Eq. (2) one by one; order is (distance, id); ids are distinct and lie in the
+    target set / the probed lists;
+  * index parity on samples: Eq. (1) codes and a(n) of sampled rows equal the oracle's, the
+    posting lists partition the identifiers in ascending order.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from helpers import check_topk, t2n
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rii():
+    import paper_1808_03969_amd as r
+    r.load_library()
+    assert torch.cuda.is_available()
+    return r
+
+
+def build(rii, name, **kw):
+    from paper_1808_03969_amd import workloads
+    cfg = workloads.CONFIGS[name]
+    w = workloads.build(cfg, **kw)
+    torch.cuda.synchronize()
+    w["codes"] = w["index"].get_codes()
+    w["q_host"] = t2n(w["q"])
+    if cfg.K:
+        w["coarse"], w["off"], w["lids"], w["assign"] = w["index"].get_lists()
+    return w
+
+
+def certify(oracle, A, codes, ids, dist, pool=None):
+    """Every returned pair re-derived by the oracle; sorted by (distance, id); distinct; in `pool`."""
+    ok = ids >= 0
+    got = ids[ok]
+    assert len(set(got.tolist())) == len(got), "duplicate ids"
+    ref = oracle.adc(A, codes, got.astype(np.int32)) if len(got) else np.zeros(0, np.float32)
+    assert np.array_equal(dist[ok], ref), "returned distance is not the ADC distance of the returned id"
+    assert np.all(np.isinf(dist[~ok]))
+    d = dist[ok]
+    assert np.all((d[1:] > d[:-1]) | ((d[1:] == d[:-1]) & (got[1:] > got[:-1]))), "order is not (distance, id)"
+    if pool is not None:
+        assert np.all(np.isin(got, pool)), "result outside the allowed identifiers"
+
+
+def check_index_samples(oracle, w, n_rows=2000, seed=1):
+    cfg, N = w["cfg"], w["N"]
+    from paper_1808_03969_amd import workloads
+    rows = np.sort(t2n(synth.sample_rows(seed, min(N, 1 << 22), n_rows)))  # sampled from the leading rows
+    # Eq. (1): regenerate the sampled vectors on the GPU (same generator, same device), encode with the oracle
+    for r in rows[:: max(1, n_rows // 64)]:
+        x = t2n(workloads.rows(cfg, 1000 + cfg.c, int(r), int(r) + 1, "cuda"))
+        assert np.array_equal(oracle.encode(w["cb"], x)[0], w["codes"][r])
+    if cfg.K:
+        T = oracle.sym_table(w["cb"])
+        a_ref = oracle.assign(T, w["codes"][rows], w["coarse"])
+        assert np.array_equal(a_ref, w["assign"][rows]), "a(n) differs from the oracle"
+        off, lids = w["off"], w["lids"]
+        assert off[0] == 0 and off[-1] == N
+        cnt = np.bincount(lids, minlength=N)
+        assert cnt.min() == 1 and cnt.max() == 1, "posting lists are not a partition"
+        seg = np.repeat(np.arange(cfg.K), np.diff(off))
+        assert np.array_equal(w["assign"][lids], seg), "an identifier sits in the wrong list"
+        inside = np.diff(lids) > 0
+        boundary = np.zeros(N - 1, dtype=bool)
+        boundary[off[1:-1][(off[1:-1] > 0) & (off[1:-1] < N)] - 1] = True
+        assert np.all(inside | boundary), "a posting list is not ascending"
+
+
+def test_c1_tiny_linear(rii, oracle_lib):
+    w = build(rii, "c1")
+    lut = rii.rii_build_lut(w["index"], w["q"])
+    ids, dist = rii.rii_adc_scan_linear(w["index"], lut, 10)
+    torch.cuda.synchronize()
+    A = oracle_lib.lut(w["cb"], w["q_host"])
+    assert np.array_equal(t2n(lut), A)
+    x = t2n(synth.gaussian(1001, 0, w["N"], 128))
+    assert np.array_equal(oracle_lib.encode(w["cb"], x), w["codes"])  # whole database
+    for i in range(w["Q"]):
+        ref = oracle_lib.linear_scan(A[i], w["codes"], 10)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
+@pytest.fixture(scope="module")
+def c2(rii):
+    return build(rii, "c2")
+
+
+def test_c2_sift_shaped_linear_and_ivf(rii, oracle_lib, c2):
+    w = c2
+    index, Q, R = w["index"], w["Q"], 100
+    check_index_samples(oracle_lib, w)
+    lut = rii.rii_build_lut(index, w["q"])
+    A = oracle_lib.lut(w["cb"], w["q_host"])
+    ids, dist = rii.rii_adc_scan_linear(index, lut, R)           # all 10,000 queries in one launch
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    for i in range(Q):
+        certify(oracle_lib, A[i], w["codes"], ids[i], dist[i])
+    for i in range(0, Q, 50):                                    # 200 queries through Alg. 1
+        ref = oracle_lib.linear_scan(A[i], w["codes"], R)
+        check_topk(ids[i], dist[i], ref[0], ref[1])
+    one = rii.rii_adc_scan_linear(index, lut[7:8], R)            # the one-query-per-launch shape
+    torch.cuda.synchronize()
+    assert np.array_equal(t2n(one[0])[0], ids[7]) and np.array_equal(t2n(one[1])[0], dist[7])
+    for nprobe in (1, 8, 32):
+        probe, d0 = rii.rii_coarse_assign(index, lut, nprobe)
+        iv = rii.rii_adc_scan_ivf(index, lut, probe, R)
+        torch.cuda.synchronize()
+        iv_i, iv_d, probe = t2n(iv[0]), t2n(iv[1]), t2n(probe)
+        for i in range(0, Q, 10):                                # 1,000 queries through Alg. 2
+            ref = oracle_lib.inverted_index(A[i], w["codes"], w["coarse"], w["off"], w["lids"], R, nprobe)
+            check_topk(iv_i[i], iv_d[i], ref[0], ref[1])
+            rk = oracle_lib.coarse_rank(A[i], w["coarse"], nprobe)
+            assert np.array_equal(probe[i], rk[0])
+        for i in range(1, Q, 97):
+            pool = np.concatenate([w["lids"][w["off"][k]:w["off"][k + 1]] for k in probe[i]])
+            certify(oracle_lib, A[i], w["codes"], iv_i[i], iv_d[i], pool=pool)
+
+
+def test_c3_subset_search_and_switch(rii, oracle_lib, c2):
+    w = c2
+    index, N, K, R = w["index"], w["N"], w["cfg"].K, 100
+    Q = 1000
+    q = w["q"][:Q].contiguous()
+    lut = rii.rii_build_lut(index, q)
+    A = oracle_lib.lut(w["cb"], w["q_host"][:Q])
+    for S in (100, 10_000, 100_000, 1_000_000):
+        tids, toff = synth.subset_batch(5003, N, [S] * Q, "cuda")
+        ids, dist = rii.rii_adc_scan_subset(index, lut, tids, toff, S, R)
+        torch.cuda.synchronize()
+        ids, dist, th, to = t2n(ids), t2n(dist), t2n(tids), t2n(toff)
+        step = 10 if S <= 100_000 else 50
+        for i in range(0, Q, step):
+            Sq = th[to[i]:to[i + 1]]
+            ref = oracle_lib.linear_scan(A[i], w["codes"], R, S=Sq)
+            check_topk(ids[i], dist[i], ref[0], ref[1])
+        for i in range(3, Q, 41):
+            certify(oracle_lib, A[i], w["codes"], ids[i], dist[i], pool=th[to[i]:to[i + 1]])
+        # Alg. 3: inverted index with the target filter above theta, linear scan below
+        for theta, L in ((20_000, N // K), (20_000, 5 * (N // K))):
+            index.set_threshold(theta)
+            qi, qd = rii.rii_query(index, q, R, tids, toff, S, L)
+            torch.cuda.synchronize()
+            qi, qd = t2n(qi), t2n(qd)
+            for i in range(0, Q, 25 if S <= 100_000 else 100):
+                Sq = th[to[i]:to[i + 1]]
+                ref = oracle_lib.query(w["cb"], w["q_host"][i], w["codes"], w["coarse"], w["off"], w["lids"], R, L,
+                                       theta, S=Sq)
+                assert ref[2] == (0 if S < theta else 1)
+                check_topk(qi[i], qd[i], ref[0], ref[1])
+        index.set_threshold(0)
+        del tids, toff
+
+
+def test_c4_deep_shaped_with_additions(rii, oracle_lib):
+    from paper_1808_03969_amd import workloads
+    w = build(rii, "c4")
+    cfg, index, N, R = w["cfg"], w["index"], w["N"], 100
+    check_index_samples(oracle_lib, w)
+    Q = w["Q"]
+    lut = rii.rii_build_lut(index, w["q"])
+    A = oracle_lib.lut(w["cb"], w["q_host"])
+    ids, dist = rii.rii_adc_scan_linear(index, lut, R)
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    for i in range(0, Q, 20):
+        certify(oracle_lib, A[i], w["codes"], ids[i], dist[i])
+    for i in range(0, Q, 500):                                   # 20 queries through Alg. 1 (1.6e8 look-ups each)
+        ref = oracle_lib.linear_scan(A[i], w["codes"], R)
+        check_topk(ids[i], dist[i], ref[0], ref[1])
+
+    def check_ivf(codes, coarse, off, lids, nprobes, every):
+        for nprobe in nprobes:
+            probe, _ = rii.rii_coarse_assign(index, lut, nprobe)
+            iv = rii.rii_adc_scan_ivf(index, lut, probe, R)
+            torch.cuda.synchronize()
+            for i in range(0, Q, every):
+                ref = oracle_lib.inverted_index(A[i], codes, coarse, off, lids, R, nprobe)
+                check_topk(t2n(iv[0])[i], t2n(iv[1])[i], ref[0], ref[1])
+
+    check_ivf(w["codes"], w["coarse"], w["off"], w["lids"], (16, 64), 100)
+    # 20 % new vectors from shifted components, encoded with the old code books (Sec. 5.4 shape)
+    n_add = N // 5
+    for r0 in range(0, n_add, 1_000_000):
+        x = workloads.rows(cfg, 6000 + cfg.c, r0, min(n_add, r0 + 1_000_000), "cuda", shift=0.5)
+        index.add(rii.rii_encode_device(index, x))
+    codes2 = index.get_codes()
+    coarse2, off2, lids2, a2 = index.get_lists()
+    assert len(codes2) == N + n_add and np.array_equal(codes2[:N], w["codes"]) and np.array_equal(coarse2, w["coarse"])
+    assert np.array_equal(a2[:N], w["assign"])                   # old items keep their lists
+    T = oracle_lib.sym_table(w["cb"])
+    rows = N + np.sort(t2n(synth.sample_rows(2, n_add, 1500)))
+    assert np.array_equal(oracle_lib.assign(T, codes2[rows], coarse2), a2[rows])
+    off_ref, lids_ref = oracle_lib.build_lists(a2, cfg.K)
+    assert np.array_equal(off2, off_ref) and np.array_equal(lids2, lids_ref)
+    check_ivf(codes2, coarse2, off2, lids2, (16,), 250)          # before list re-assignment
+    lin2 = rii.rii_adc_scan_linear(index, lut[:64].contiguous(), R)
+    torch.cuda.synchronize()
+    for i in range(0, 64, 16):
+        ref = oracle_lib.linear_scan(A[i], codes2, R)
+        check_topk(t2n(lin2[0])[i], t2n(lin2[1])[i], ref[0], ref[1])
+    index.reconfigure(cfg.K, iters=2, seed=4004)                 # Alg. 4
+    coarse3, off3, lids3, a3 = index.get_lists()
+    assert np.array_equal(oracle_lib.assign(T, codes2[rows], coarse3), a3[rows])
+    off_ref, lids_ref = oracle_lib.build_lists(a3, cfg.K)
+    assert np.array_equal(off3, off_ref) and np.array_equal(lids3, lids_ref)
+    check_ivf(codes2, coarse3, off3, lids3, (16, 64), 250)       # after list re-assignment
+
+
+def test_c5_billion_scale_shard(rii, oracle_lib):
+    w = build(rii, "c5")
+    cfg, index, N, Q, R = w["cfg"], w["index"], w["N"], w["Q"], 100
+    check_index_samples(oracle_lib, w, n_rows=1000)
+    lut = rii.rii_build_lut(index, w["q"])
+    A = oracle_lib.lut(w["cb"], w["q_host"])
+    ids, dist = rii.rii_adc_scan_linear(index, lut, R)           # the batched launch bench.py times
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    for i in range(0, Q, 10):
+        certify(oracle_lib, A[i], w["codes"], ids[i], dist[i])
+    sample = (0, 3333, 9999)
+    for i in sample:                                             # 3.2e9 look-ups per query
+        ref = oracle_lib.linear_scan(A[i], w["codes"], R)
+        check_topk(ids[i], dist[i], ref[0], ref[1])
+        one = rii.rii_adc_scan_linear(index, lut[i:i + 1], R)    # one query per launch (2,035 blocks)
+        torch.cuda.synchronize()
+        assert np.array_equal(t2n(one[0])[0], ref[0]) and np.array_equal(t2n(one[1])[0], ref[1])
+    probe, _ = rii.rii_coarse_assign(index, lut, 64)
+    iv = rii.rii_adc_scan_ivf(index, lut, probe, R)
+    torch.cuda.synchronize()
+    for i in range(0, Q, 200):
+        ref = oracle_lib.inverted_index(A[i], w["codes"], w["coarse"], w["off"], w["lids"], R, 64)
+        check_topk(t2n(iv[0])[i], t2n(iv[1])[i], ref[0], ref[1])
+    Qs, S = 256, 1_000_000
+    tids, toff = synth.subset_batch(5005, N, [S] * Qs, "cuda")
+    sub = rii.rii_adc_scan_subset(index, lut[:Qs].contiguous(), tids, toff, S, R)
+    L = 64 * (N // cfg.K)
+    qry = rii.rii_query(index, w["q"][:Qs].contiguous(), R, L=L)
+    torch.cuda.synchronize()
+    th, to = t2n(tids), t2n(toff)
+    for i in range(0, Qs, 8):
+        Sq = th[to[i]:to[i + 1]]
+        ref = oracle_lib.linear_scan(A[i], w["codes"], R, S=Sq)
+        check_topk(t2n(sub[0])[i], t2n(sub[1])[i], ref[0], ref[1])
+        certify(oracle_lib, A[i], w["codes"], t2n(sub[0])[i], t2n(sub[1])[i], pool=Sq)
+        ref = oracle_lib.query(w["cb"], w["q_host"][i], w["codes"], w["coarse"], w["off"], w["lids"], R, L, 0)
+        assert ref[2] == 1
+        check_topk(t2n(qry[0])[i], t2n(qry[1])[i], ref[0], ref[1])
