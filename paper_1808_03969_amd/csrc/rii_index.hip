@@ -14,12 +14,14 @@
 #include "rii_internal.h"
 
 extern "C" int rii_internal_sym_table(const rii_index* idx, hipStream_t st);
-extern "C" int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, const uint8_t* super,
-                                          int G, const float* radius, const uint8_t* coarse_g, const int32_t* perm_g,
-                                          const int32_t* group_off, int32_t* assign_out,
+extern "C" int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base,
+                                   const uint8_t* coarse, int K, int32_t* assign_out, hipStream_t st);
+extern "C" int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base,
+                                          const uint8_t* super, int G, const float* radius, const uint8_t* coarse_g,
+                                          const int32_t* perm_g, const int32_t* group_off, int32_t* assign_out,
                                           unsigned long long* visited_total, hipStream_t st);
-extern "C" int rii_internal_gather_rows(const uint8_t* codes, const int32_t* list_ids, int64_t N, int M,
-                                        uint8_t* out, hipStream_t st);
+extern "C" int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, const int32_t* ids, int64_t n, int M,
+                                      uint8_t* out, int64_t out_rot, hipStream_t st);
 
 namespace {
 
@@ -31,6 +33,7 @@ void free_dev(T*& p) {
 
 void drop_lists(rii_index* idx) {
   free_dev(idx->d_coarse);
+  free_dev(idx->d_coarse_st);
   free_dev(idx->d_list_off);
   free_dev(idx->d_list_ids);
   free_dev(idx->d_assign);
@@ -48,19 +51,23 @@ int install_lists(rii_index* idx, const uint8_t* coarse, int K, const std::vecto
   const int M = idx->M;
   drop_lists(idx);
   RII_HIP(hipMalloc(&idx->d_coarse, (size_t)K * M));
+  RII_HIP(hipMalloc(&idx->d_coarse_st, (size_t)K * M));
   RII_HIP(hipMalloc(&idx->d_list_off, (size_t)(K + 1) * 8));
   RII_HIP(hipMalloc(&idx->d_list_ids, std::max<size_t>((size_t)N * 4, 4)));
   RII_HIP(hipMalloc(&idx->d_assign, std::max<size_t>((size_t)N * 4, 4)));
   RII_HIP(hipMalloc(&idx->d_codes_list, std::max<size_t>((size_t)N * M, 16)));
   RII_HIP(hipMemcpy(idx->d_coarse, coarse, (size_t)K * M, hipMemcpyHostToDevice));
+  int rc = rii_internal_copy_rows(idx->d_coarse, -1, nullptr, K, M, idx->d_coarse_st, 0, nullptr);
+  if (rc) return rc;
   RII_HIP(hipMemcpy(idx->d_list_off, off.data(), (size_t)(K + 1) * 8, hipMemcpyHostToDevice));
   if (N > 0) {
     RII_HIP(hipMemcpy(idx->d_list_ids, ids.data(), (size_t)N * 4, hipMemcpyHostToDevice));
     RII_HIP(hipMemcpy(idx->d_assign, assign.data(), (size_t)N * 4, hipMemcpyHostToDevice));
-    int rc = rii_internal_gather_rows(idx->d_codes, idx->d_list_ids, N, M, idx->d_codes_list, nullptr);
+    // row p of the list-ordered copy = code of identifier list_ids[p], stored form (rotated by p)
+    rc = rii_internal_copy_rows(idx->d_codes, 0, idx->d_list_ids, N, M, idx->d_codes_list, 0, nullptr);
     if (rc) return rc;
-    RII_HIP(hipDeviceSynchronize());
   }
+  RII_HIP(hipDeviceSynchronize());
   idx->h_coarse.assign(coarse, coarse + (size_t)K * M);
   idx->h_list_off = off;
   idx->K = K;
@@ -159,15 +166,17 @@ int make_groups(rii_index* idx, const uint8_t* coarse, int K, CentreGroups& g) {
 }
 
 // a(n) for n device-resident codes `rows` under the host coarse centres `coarse`; the result
-// stays on the device (d_out, n entries).  Brute force for small K, pruned search
+// stays on the device (d_out, n entries).  rot_base >= 0: `rows` are stored rows rot_base.. (stored
+// form), rot_base < 0: plain codes.  Brute force for small K, pruned search
 // (same result) for large K.
-int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, const uint8_t* coarse, int K, int32_t* d_out) {
+int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, int64_t rot_base, const uint8_t* coarse, int K,
+                    int32_t* d_out) {
   if (n == 0) return RII_OK;
   if (K >= kPruneMinK) {
     CentreGroups g;
     int rc = make_groups(idx, coarse, K, g);
     if (rc) return rc;
-    rc = rii_internal_assign_pruned(idx, rows, n, g.d_super, g.G, g.d_radius, g.d_coarse_g, g.d_perm_g,
+    rc = rii_internal_assign_pruned(idx, rows, n, rot_base, g.d_super, g.G, g.d_radius, g.d_coarse_g, g.d_perm_g,
                                     g.d_group_off, d_out, nullptr, nullptr);
     if (rc) return rc;
     RII_HIP(hipDeviceSynchronize());
@@ -177,7 +186,7 @@ int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, const uint8_
   RII_HIP(hipMalloc(&d_coarse, (size_t)K * idx->M));
   int rc = RII_OK;
   if (hipMemcpy(d_coarse, coarse, (size_t)K * idx->M, hipMemcpyHostToDevice) != hipSuccess) rc = RII_ERR_DEVICE;
-  if (!rc) rc = rii_assign(idx, rows, n, d_coarse, K, d_out, nullptr);
+  if (!rc) rc = rii_internal_assign(idx, rows, n, rot_base, d_coarse, K, d_out, nullptr);
   if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
   (void)hipFree(d_coarse);
   return rc;
@@ -187,7 +196,7 @@ int assign_stored(rii_index* idx, int64_t first, int64_t n, const uint8_t* coars
   if (n == 0) return RII_OK;
   int32_t* d_out = nullptr;
   RII_HIP(hipMalloc(&d_out, (size_t)n * 4));
-  int rc = assign_rows_dev(idx, idx->d_codes + first * idx->M, n, coarse, K, d_out);
+  int rc = assign_rows_dev(idx, idx->d_codes + first * idx->M, n, first, coarse, K, d_out);
   if (!rc && hipMemcpy(assign_host, d_out, (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
   (void)hipFree(d_out);
   return rc;
@@ -274,8 +283,24 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
     idx->d_codes = nb;
     idx->cap = ncap;
   }
-  RII_HIP(hipMemcpy(idx->d_codes + idx->N * M, codes, (size_t)n * M,
-                    mem == RII_MEM_HOST ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice));
+  {
+    // bring the new rows into stored form (row r rotated by r bytes when M is 8, 16 or 32)
+    const uint8_t* src = codes;
+    uint8_t* stage = nullptr;
+    if (mem == RII_MEM_HOST) {
+      RII_HIP(hipMalloc(&stage, (size_t)n * M));
+      if (hipMemcpy(stage, codes, (size_t)n * M, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(stage);
+        return RII_ERR_DEVICE;
+      }
+      src = stage;
+    }
+    int rc = rii_internal_copy_rows(src, -1, nullptr, n, M, idx->d_codes + idx->N * M, idx->N, nullptr);
+    if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
+    if (stage) (void)hipFree(stage);
+    if (rc) return rc;
+  }
   const int64_t oldN = idx->N;
   idx->N += n;
   if (idx->K > 0) {
@@ -344,24 +369,18 @@ int rii_index_reconfigure(rii_index_t* idx, int K, int iters, uint64_t seed) {
   std::vector<int64_t> rows = rii_host::sample_without_replacement(N, ns, seed);
   std::vector<uint8_t> sample((size_t)ns * M);
   {
-    // fetch the sampled rows: whole array when the sample is dense, row by row otherwise
-    if (ns * 4 >= N) {
-      std::vector<uint8_t> all((size_t)N * M);
-      RII_HIP(hipMemcpy(all.data(), idx->d_codes, all.size(), hipMemcpyDeviceToHost));
-      for (int64_t i = 0; i < ns; ++i) std::memcpy(&sample[i * M], &all[rows[i] * M], M);
-    } else {
-      std::vector<int32_t> r32(rows.begin(), rows.end());
-      int32_t* d_rows = nullptr;
-      uint8_t* d_tmp = nullptr;
-      RII_HIP(hipMalloc(&d_rows, (size_t)ns * 4));
-      RII_HIP(hipMalloc(&d_tmp, (size_t)ns * M));
-      RII_HIP(hipMemcpy(d_rows, r32.data(), (size_t)ns * 4, hipMemcpyHostToDevice));
-      int rc = rii_internal_gather_rows(idx->d_codes, d_rows, ns, M, d_tmp, nullptr);
-      if (rc) return rc;
-      RII_HIP(hipMemcpy(sample.data(), d_tmp, sample.size(), hipMemcpyDeviceToHost));
-      (void)hipFree(d_rows);
-      (void)hipFree(d_tmp);
-    }
+    // fetch the sampled rows in plain form
+    std::vector<int32_t> r32(rows.begin(), rows.end());
+    int32_t* d_rows = nullptr;
+    uint8_t* d_tmp = nullptr;
+    RII_HIP(hipMalloc(&d_rows, (size_t)ns * 4));
+    RII_HIP(hipMalloc(&d_tmp, (size_t)ns * M));
+    RII_HIP(hipMemcpy(d_rows, r32.data(), (size_t)ns * 4, hipMemcpyHostToDevice));
+    int rc = rii_internal_copy_rows(idx->d_codes, 0, d_rows, ns, M, d_tmp, -1, nullptr);
+    if (rc) return rc;
+    RII_HIP(hipMemcpy(sample.data(), d_tmp, sample.size(), hipMemcpyDeviceToHost));
+    (void)hipFree(d_rows);
+    (void)hipFree(d_tmp);
   }
   // initial centres: the first K distinct codes of the sample in a seeded order
   std::vector<uint8_t> coarse((size_t)K * M);
@@ -398,7 +417,7 @@ int rii_index_reconfigure(rii_index_t* idx, int K, int iters, uint64_t seed) {
     RII_HIP(hipMemcpy(d_sample, sample.data(), sample.size(), hipMemcpyHostToDevice));
     std::vector<int32_t> assign(ns);
     for (int it = 0; it < iters; ++it) {
-      int rc2 = assign_rows_dev(idx, d_sample, ns, coarse.data(), K, d_assign);
+      int rc2 = assign_rows_dev(idx, d_sample, ns, -1, coarse.data(), K, d_assign);
       if (rc2) return rc2;
       RII_HIP(hipMemcpy(assign.data(), d_assign, (size_t)ns * 4, hipMemcpyDeviceToHost));
       rii_host::update_centres(sample.data(), ns, assign.data(), sym.data(), M, K, coarse.data());
@@ -426,9 +445,18 @@ int rii_index_get_codes(const rii_index_t* idx, int64_t first, int64_t n, uint8_
       (mem != RII_MEM_HOST && mem != RII_MEM_DEVICE))
     return RII_ERR_INVALID_ARG;
   if (n == 0) return RII_OK;
-  RII_HIP(hipMemcpy(codes_out, idx->d_codes + first * idx->M, (size_t)n * idx->M,
-                    mem == RII_MEM_HOST ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice));
-  return RII_OK;
+  const int M = idx->M;
+  uint8_t* dst = codes_out;
+  uint8_t* stage = nullptr;
+  if (mem == RII_MEM_HOST) {
+    RII_HIP(hipMalloc(&stage, (size_t)n * M));
+    dst = stage;
+  }
+  int rc = rii_internal_copy_rows(idx->d_codes + first * M, first, nullptr, n, M, dst, -1, nullptr);  // plain form
+  if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
+  if (!rc && stage && hipMemcpy(codes_out, stage, (size_t)n * M, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
+  if (stage) (void)hipFree(stage);
+  return rc;
 }
 
 }  // extern "C"

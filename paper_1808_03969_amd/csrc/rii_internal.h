@@ -18,12 +18,15 @@ struct rii_index {
 
   float* d_cb = nullptr;          // [M][256][Ds] codebooks
   float* d_sym = nullptr;         // [M][256][256] code-word-to-code-word squared distances (lazy)
-  uint8_t* d_codes = nullptr;     // [cap][M] codes in identifier order (the linear array)
-  uint8_t* d_coarse = nullptr;    // [K][M] coarse centres (PQ codes)
+  // "Stored" code arrays (d_codes, d_codes_list, d_coarse_st) keep row r rotated by r bytes when
+  // M is 8, 16 or 32 (stored[r][t] = code[r][(t + r) % M]), plain otherwise; see rii_kernels.hip.
+  uint8_t* d_codes = nullptr;     // [cap][M] codes in identifier order (the linear array), stored form
+  uint8_t* d_coarse = nullptr;    // [K][M] coarse centres (PQ codes), plain
+  uint8_t* d_coarse_st = nullptr; // [K][M] coarse centres, stored form (what the coarse ranking scans)
   int64_t* d_list_off = nullptr;  // [K+1]
   int32_t* d_list_ids = nullptr;  // [N] identifiers, list after list
   int32_t* d_assign = nullptr;    // [N] a(n)
-  uint8_t* d_codes_list = nullptr;  // [N][M] codes permuted into list order (row p = code of d_list_ids[p])
+  uint8_t* d_codes_list = nullptr;  // [N][M] codes permuted into list order (row p = code of d_list_ids[p]), stored form
   std::vector<uint8_t> h_coarse;    // host mirror of the coarse centres
   std::vector<int64_t> h_list_off;  // host mirror of the list offsets
   int64_t max_list_len = 0;

@@ -30,7 +30,7 @@ constexpr int kSelCap = 2048;          // keys held per block between compaction
 #define RII_ROWS_PER_LANE 4
 #endif
 #ifndef RII_WANT_BLOCKS
-#define RII_WANT_BLOCKS 2048
+#define RII_WANT_BLOCKS 256
 #endif
 #ifndef RII_TILE_STRIDED
 #define RII_TILE_STRIDED 0
@@ -40,7 +40,7 @@ constexpr int kSelCap = 2048;          // keys held per block between compaction
 #endif
 constexpr int kScanThreads = RII_SCAN_THREADS;
 constexpr int kRowsPerLane = RII_ROWS_PER_LANE;  // rows scored per lane per tile
-constexpr int kPrepassBlocks = 64;               // blocks (tiles) of the bound-seeding pass, per query
+constexpr int kPrepassBlocks = 256;              // blocks (tiles) of the bound-seeding pass, per query
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kOrdMax = 0xFFFFFFFFu;
 
@@ -188,6 +188,95 @@ __device__ __forceinline__ float adc_row(const float* __restrict__ A, const uint
   return d;
 }
 
+// ------------------------------------------------------------------ rotated rows (M = 8, 16, 32)
+// For these M the stored code arrays keep row r rotated by r bytes: stored[r][t] = code[r][(t + r) % M].
+// The table sits in LDS as T[z][s], 64 slots of 4 bytes per code value z, slot s holding
+// A[s % M][z].  A lane scoring row r reads slot (r % 32) + t at step t, i.e. sub-space (r + t) % M
+// -- exactly the sub-space stored byte t belongs to.  32 consecutive rows (one per lane) hit 32
+// different LDS banks at every step whatever the code values are: no bank conflicts, and the byte
+// position t is the same in all lanes, so the address is one v_perm_b32 away from the loaded dword
+// (row stride 256 bytes puts z into byte 1).
+// The sum then runs over the sub-spaces in rotated order; its fp32 rounding differs from the
+// ascending-m sum the results are defined with, so it is used as a filter only: a row whose
+// rotated sum is not above (1 + kRotEps(M)) * bound has its ascending-m sum recomputed exactly.
+__host__ __device__ constexpr bool rot_m(int M) { return M == 8 || M == 16 || M == 32; }
+// LDS bytes of one query's table: 256 x 64 slots in the rotated layout, [M][256] otherwise.
+__host__ __device__ constexpr size_t table_bytes(int M) { return rot_m(M) ? (size_t)65536 : (size_t)M * 1024; }
+// LDS of the bound-seeding kernel: the table plus, in the rotated layout, the staging copy used to fill it.
+__host__ __device__ constexpr size_t tau0_lds(int M) { return table_bytes(M) + (rot_m(M) ? (size_t)M * 1024 : 0); }
+
+// Both sums are within (M-1) u / (1 - (M-1) u) of the exact real sum of non-negative terms
+// (u = 2^-24), so they differ by less than a factor 1 + (M-1) 2^-23; M 2^-22 leaves room for
+// the rounding of the product bound * (1 + eps) itself.
+__device__ __forceinline__ float rot_eps(int M) { return (float)M * 2.384185791015625e-07f; }
+
+// Fill T from the query's table A = lut[M][256].  The table is first copied to `stage` (LDS,
+// M KB, coalesced reads), then transposed into T along diagonals: lane l of a group of 32 moves
+// element (z0 + l, (s0 + l) % 64), so both the read (bank z % 32) and the write (bank s % 32) touch 32
+// different banks.  Block-wide; ends with a barrier.  `stage` may be reused afterwards.
+template <int MT>
+__device__ __forceinline__ void fill_table_rot(float* T, float* stage, const float* __restrict__ lut) {
+  for (int i = threadIdx.x; i < MT * 256; i += blockDim.x) stage[i] = lut[i];
+  __syncthreads();
+  for (int it = threadIdx.x; it < 256 * 64; it += blockDim.x) {
+    const int l = it & 31, blk = it >> 5;
+    const int s0 = blk & 63, z0 = (blk >> 6) << 5;
+    const int z = z0 + l, s = (s0 + l) & 63;
+    T[z * 64 + s] = stage[(s & (MT - 1)) * 256 + z];
+  }
+  __syncthreads();
+}
+
+// Rotated-order sum for one stored row; lanebase = (row % 32) * 4.
+template <int MT>
+__device__ __forceinline__ float adc_row_rot(const float* T, const uint8_t* __restrict__ row, uint32_t lanebase) {
+  uint32_t w[MT / 4];
+  if constexpr (MT == 8) {
+    uint2 v = *reinterpret_cast<const uint2*>(row);
+    w[0] = v.x; w[1] = v.y;
+  } else {
+    const uint4* p = reinterpret_cast<const uint4*>(row);
+#pragma unroll
+    for (int j = 0; j < MT / 16; ++j) {
+      uint4 v = p[j];
+      w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+    }
+  }
+  float d = 0.f;
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    // byte 0 <- lanebase, byte 1 <- code byte t, bytes 2,3 <- 0
+    uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lanebase, 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
+    d = __fadd_rn(d, *reinterpret_cast<const float*>(reinterpret_cast<const char*>(T) + addr + t * 4));
+  }
+  return d;
+}
+
+// Ascending-m sum for stored row number r (rotated storage), table in the T layout.
+template <int MT>
+__device__ __forceinline__ float adc_row_exact_rot(const float* T, const uint8_t* __restrict__ row, int64_t r) {
+  float d = 0.f;
+#pragma unroll 4
+  for (int m = 0; m < MT; ++m) d = __fadd_rn(d, T[(int)row[(m - (int)r) & (MT - 1)] * 64 + m]);
+  return d;
+}
+
+// Ascending-m sum for stored row number r (rotated storage), table in the plain [m][z] layout.
+template <int MT>
+__device__ __forceinline__ float adc_row_unrot(const float* A, const uint8_t* __restrict__ row, int64_t r) {
+  float d = 0.f;
+#pragma unroll 4
+  for (int m = 0; m < MT; ++m) d = __fadd_rn(d, A[m * 256 + row[(m - (int)r) & (MT - 1)]]);
+  return d;
+}
+
+// Upper bound, as a float, for the rotated sum of any row whose ascending-m sum has an image <= bound.
+__device__ __forceinline__ float rot_filter(uint32_t bound, float eps) {
+  if (bound == kOrdMax) return __uint_as_float(0x7F800000u);
+  float f = float_of_ord(bound);
+  return __fadd_rn(f, __fmul_rn(f, eps));
+}
+
 // ------------------------------------------------------------------ scan (Alg. 1)
 struct ScanArgs {
   const uint8_t* codes;          // [N][M]
@@ -261,7 +350,9 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(ScanArgs a) {
       key[r] = kKeyMax;
       if (i < r1) {
         int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
-        float d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
+        float d;
+        if constexpr (rot_m(MT)) d = adc_row_unrot<MT>(A, a.codes + (int64_t)id * M, id);
+        else d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
         key[r] = make_key(d, id);
         if ((uint32_t)(key[r] >> 32) <= tau) pend |= 1u << r;
       }
@@ -387,14 +478,26 @@ __global__ __launch_bounds__(kScanThreads) void k_tau0(ScanArgs a) {
   uint32_t best = kOrdMax;
   if (r0 < nrows) {  // block-uniform
     const float* lut = a.lut + q * M * 256;
-    for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
-    __syncthreads();
+    if constexpr (rot_m(MT)) {
+      fill_table_rot<MT>(A, A + 256 * 64, lut);
+    } else {
+      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
+      __syncthreads();
+    }
 #pragma unroll
     for (int r = 0; r < kRowsPerLane; ++r) {
       int64_t i = r0 + (int64_t)r * blockDim.x + tid;
       if (i < nrows) {
         int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
-        uint32_t o = ord_of(adc_row<MT>(A, a.codes + (int64_t)id * M, M));
+        float d;
+        if constexpr (rot_m(MT)) {
+          // rotated-order sum, raised so that it bounds the row's ascending-m sum from above
+          d = adc_row_rot<MT>(A, a.codes + (int64_t)id * M, ((uint32_t)id & 31u) << 2);
+          d = __fadd_rn(d, __fmul_rn(d, rot_eps(MT)));
+        } else {
+          d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
+        }
+        uint32_t o = ord_of(d);
         if (o < best) best = o;
       }
     }
@@ -511,7 +614,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
   extern __shared__ __align__(16) uint8_t smem[];
   const int M = MT ? MT : a.M;
   float* A = reinterpret_cast<float*>(smem);
-  uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + (size_t)M * 1024);  // [waves + 1][kWaveCap]
+  uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + table_bytes(M));  // [waves + 1][kWaveCap]
   __shared__ int s_total, s_off, s_last;
   __shared__ uint32_t s_tg;
 
@@ -530,18 +633,30 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
     nrows = a.target_offsets[q + 1] - o0;
     tids = a.target_ids + o0;
   }
+#if RII_TILE_STRIDED
+  // tiles are dealt to the query's blocks round-robin, so that the blocks resident at any time
+  // read one moving window of the array (DRAM pages are shared by neighbouring requests)
+  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane * gridDim.x;
+  const int64_t r0 = (int64_t)blockIdx.x * blockDim.x * kRowsPerLane;
+  const int64_t r1 = nrows;
+#else
+  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
   const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
   const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
+#endif
   uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
   const int k = a.k;
 
   if (r0 < r1) {  // block-uniform
     const float* lut = a.lut + q * M * 256;
-    for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
-    __syncthreads();
+    if constexpr (rot_m(MT)) {
+      fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), lut);  // the wave buffers are not in use yet
+    } else {
+      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
+      __syncthreads();
+    }
     int cnt = 0;
     uint32_t tau = kOrdMax;
-    const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
     // The query's shared bound is re-read once per tile by the block's first wave only and
     // passed on through LDS (a plain word, read without synchronisation: a stale value is
     // still a valid bound); thousands of waves polling one address would serialise on it.
@@ -553,16 +668,44 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
       uint32_t fresh = kOrdMax;
       if (wave == 0) fresh = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const uint32_t bound = tg < tau ? tg : tau;
+      if constexpr (rot_m(MT)) {
+        // filter on the conflict-free rotated-order sum; exact ascending-m sum for the few rows that pass
+        const float fb = rot_filter(bound, rot_eps(MT));
+        int32_t rid[kRowsPerLane];
+        uint32_t maybe = 0;
 #pragma unroll
-      for (int r = 0; r < kRowsPerLane; ++r) {
-        // a wave owns 64 consecutive rows of each of the tile's kRowsPerLane slices
-        int64_t i = tile + (int64_t)r * blockDim.x + tid;
-        key[r] = kKeyMax;
-        if (i < r1) {
-          int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
-          float d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
-          key[r] = make_key(d, id);
-          if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          int64_t i = tile + (int64_t)r * blockDim.x + tid;
+          key[r] = kKeyMax;
+          rid[r] = 0;
+          if (i < r1) {
+            rid[r] = MODE == kLinear ? (int32_t)i : tids[i];
+            float df = adc_row_rot<MT>(A, a.codes + (int64_t)rid[r] * M, ((uint32_t)rid[r] & 31u) << 2);
+            if (df <= fb) maybe |= 1u << r;
+          }
+        }
+        if (__ballot(maybe != 0) != 0ull) {
+#pragma unroll
+          for (int r = 0; r < kRowsPerLane; ++r) {
+            if (maybe & (1u << r)) {
+              float d = adc_row_exact_rot<MT>(A, a.codes + (int64_t)rid[r] * M, rid[r]);
+              key[r] = make_key(d, rid[r]);
+              if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          // a wave owns 64 consecutive rows of each of the tile's kRowsPerLane slices
+          int64_t i = tile + (int64_t)r * blockDim.x + tid;
+          key[r] = kKeyMax;
+          if (i < r1) {
+            int32_t id = MODE == kLinear ? (int32_t)i : tids[i];
+            float d = adc_row<MT>(A, a.codes + (int64_t)id * M, M);
+            key[r] = make_key(d, id);
+            if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
+          }
         }
       }
       if (__ballot(pend != 0) != 0ull) {
@@ -810,7 +953,7 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
   extern __shared__ __align__(16) uint8_t smem[];
   const int M = MT ? MT : a.M;
   float* A = reinterpret_cast<float*>(smem);
-  uint64_t* keys = reinterpret_cast<uint64_t*>(smem + (size_t)M * 1024);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(smem + table_bytes(M));
   __shared__ int s_cnt;
   __shared__ uint32_t s_tau;
   __shared__ int s_wave[kScanThreads / 64];
@@ -818,7 +961,8 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
   const int tid = threadIdx.x;
   const int64_t q = blockIdx.x;
   if (a.qmode && a.qmode[q] != a.want_mode) return;
-  for (int i = tid; i < M * 256; i += blockDim.x) A[i] = a.lut[q * M * 256 + i];
+  if constexpr (rot_m(MT)) fill_table_rot<MT>(A, reinterpret_cast<float*>(keys), a.lut + q * M * 256);
+  else for (int i = tid; i < M * 256; i += blockDim.x) A[i] = a.lut[q * M * 256 + i];
   if (tid == 0) {
     s_cnt = 0;
     s_tau = kOrdMax;
@@ -853,9 +997,20 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
       uint64_t key[1] = {kKeyMax};
       uint32_t pend = 0;
       if (valid) {
-        float d = adc_row<MT>(A, a.codes_list + pos * M, M);
-        key[0] = make_key(d, id);
-        if ((uint32_t)(key[0] >> 32) <= s_tau) pend = 1;
+        float d;
+        bool maybe = true;
+        if constexpr (rot_m(MT)) {
+          // the list-ordered copy is rotated by position; filter on the rotated-order sum first
+          d = adc_row_rot<MT>(A, a.codes_list + pos * M, ((uint32_t)pos & 31u) << 2);
+          maybe = d <= rot_filter(s_tau, rot_eps(MT));
+          if (maybe) d = adc_row_exact_rot<MT>(A, a.codes_list + pos * M, pos);
+        } else {
+          d = adc_row<MT>(A, a.codes_list + pos * M, M);
+        }
+        if (maybe) {
+          key[0] = make_key(d, id);
+          if ((uint32_t)(key[0] >> 32) <= s_tau) pend = 1;
+        }
       }
       sel_offer<1>(keys, &s_cnt, &s_tau, a.k, key, pend);
     }
@@ -955,7 +1110,8 @@ __global__ void k_sym_table(const float* __restrict__ cb, int Ds, float* __restr
 // the arg-min (lowest k on ties) is reduced over the block.
 template <int MT>
 __global__ __launch_bounds__(256) void k_assign(const float* __restrict__ sym, const uint8_t* __restrict__ codes,
-                                                int64_t n, int Mrt, const uint8_t* __restrict__ coarse, int K,
+                                                int64_t n, int64_t rot_base, int Mrt,
+                                                const uint8_t* __restrict__ coarse, int K,
                                                 int32_t* __restrict__ assign) {
   extern __shared__ __align__(16) uint8_t smem[];
   const int M = MT ? MT : Mrt;
@@ -966,7 +1122,8 @@ __global__ __launch_bounds__(256) void k_assign(const float* __restrict__ sym, c
     __syncthreads();
     for (int i = tid; i < M * 256; i += blockDim.x) {
       int m = i >> 8, z = i & 255;
-      A[i] = sym[((size_t)m * 256 + codes[item * M + m]) * 256 + z];
+      int pos = rot_base >= 0 ? (int)((m - (rot_base + item)) & (M - 1)) : m;  // rotated storage: see adc_row_rot
+      A[i] = sym[((size_t)m * 256 + codes[item * M + pos]) * 256 + z];
     }
     __syncthreads();
     uint64_t best = kKeyMax;
@@ -999,7 +1156,8 @@ __global__ __launch_bounds__(256) void k_assign(const float* __restrict__ sym, c
 // scored with the exact fp32 sum, so the result equals the brute-force arg-min, ties to lower k.
 template <int MT>
 __global__ __launch_bounds__(256) void k_assign_pruned(const float* __restrict__ sym, const uint8_t* __restrict__ codes,
-                                                       int64_t n, int Mrt, const uint8_t* __restrict__ super, int G,
+                                                       int64_t n, int64_t rot_base, int Mrt,
+                                                       const uint8_t* __restrict__ super, int G,
                                                        const float* __restrict__ radius,
                                                        const uint8_t* __restrict__ coarse_g,
                                                        const int32_t* __restrict__ perm_g,
@@ -1016,7 +1174,8 @@ __global__ __launch_bounds__(256) void k_assign_pruned(const float* __restrict__
     __syncthreads();
     for (int i = tid; i < M * 256; i += blockDim.x) {
       int m = i >> 8, z = i & 255;
-      A[i] = sym[((size_t)m * 256 + codes[item * M + m]) * 256 + z];
+      int pos = rot_base >= 0 ? (int)((m - (rot_base + item)) & (M - 1)) : m;  // rotated storage: see adc_row_rot
+      A[i] = sym[((size_t)m * 256 + codes[item * M + pos]) * 256 + z];
     }
     __syncthreads();
     // distances to the super-centres, bounds, nearest super-centre
@@ -1080,14 +1239,29 @@ __global__ __launch_bounds__(256) void k_assign_pruned(const float* __restrict__
   if (visited_total && visited) atomicAdd(visited_total, visited);
 }
 
-// codes_list[p] = codes[list_ids[p]]
-__global__ void k_gather_rows(const uint8_t* __restrict__ codes, const int32_t* __restrict__ list_ids, int64_t N,
-                              int M4, uint32_t* __restrict__ out) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one dword of one row
-  if (i >= N * M4) return;
-  int64_t p = i / M4;
-  int w = (int)(i - p * M4);
-  out[i] = reinterpret_cast<const uint32_t*>(codes)[(int64_t)list_ids[p] * M4 + w];
+// General row copy between plain and rotated storage, optionally gathering by identifier:
+//   source row of output row i: src = ids ? ids[i] : i;
+//   in_rot  >= 0: the source array stores row s rotated by (in_rot + s) bytes, else plain;
+//   out_rot >= 0: output row i is stored rotated by (out_rot + i) bytes, else plain.
+// One thread per output dword.
+__global__ void k_copy_rows(const uint8_t* __restrict__ in, int64_t in_rot, const int32_t* __restrict__ ids,
+                            int64_t n, int M, uint8_t* __restrict__ out, int64_t out_rot) {
+  const int M4 = M >> 2;
+  int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n * M4) return;
+  const int64_t i = g / M4;
+  const int w = (int)(g - i * M4);
+  const int64_t src = ids ? (int64_t)ids[i] : i;
+  const uint8_t* row = in + src * M;
+  uint32_t v = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    int t = 4 * w + b;                                             // output byte position
+    int m = out_rot >= 0 ? (int)((t + out_rot + i) & (M - 1)) : t;  // sub-space it holds
+    int pos = in_rot >= 0 ? (int)((m - (in_rot + src)) & (M - 1)) : m;
+    v |= (uint32_t)row[pos] << (8 * b);
+  }
+  reinterpret_cast<uint32_t*>(out)[g] = v;
 }
 
 // ------------------------------------------------------------------ host helpers
@@ -1190,16 +1364,16 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     pre.minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * nchunks * topk);
     pre.counter = pre_counter;
     dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
-    const size_t ldsw = (size_t)M * 1024 + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
     if (mode == kLinear) {
       DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kLinear>, ldsw); if (rc) return rc;
-                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kLinear>, (size_t)M * 1024); if (rc2) return rc2; }
-                      if (prepass) k_tau0<MT, kLinear><<<pgrid, kScanThreads, (size_t)M * 1024, st>>>(pre);
+                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kLinear>, tau0_lds(M)); if (rc2) return rc2; }
+                      if (prepass) k_tau0<MT, kLinear><<<pgrid, kScanThreads, tau0_lds(M), st>>>(pre);
                       k_scan_w<MT, kLinear><<<grid, kScanThreads, ldsw, st>>>(a); });
     } else {
       DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kSubset>, ldsw); if (rc) return rc;
-                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kSubset>, (size_t)M * 1024); if (rc2) return rc2; }
-                      if (prepass) k_tau0<MT, kSubset><<<pgrid, kScanThreads, (size_t)M * 1024, st>>>(pre);
+                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kSubset>, tau0_lds(M)); if (rc2) return rc2; }
+                      if (prepass) k_tau0<MT, kSubset><<<pgrid, kScanThreads, tau0_lds(M), st>>>(pre);
                       k_scan_w<MT, kSubset><<<grid, kScanThreads, ldsw, st>>>(a); });
     }
   } else {
@@ -1300,7 +1474,7 @@ static int coarse_rank(const rii_index* idx, const float* lut, int Q, int nprobe
                        int out_stride, const int* qmode, int want_mode, void* ws, hipStream_t st) {
   const int M = idx->M, K = idx->K;
   if (nprobe <= RII_MAX_TOPK) {
-    return launch_scan(idx, idx->d_coarse, K, lut, Q, kLinear, nullptr, nullptr, K, nprobe, list_ids, list_d0,
+    return launch_scan(idx, idx->d_coarse_st, K, lut, Q, kLinear, nullptr, nullptr, K, nprobe, list_ids, list_d0,
                        out_stride, qmode, want_mode, ws, st);
   }
   if (K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
@@ -1345,7 +1519,7 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
   a.lut = lut; a.probe = probe; a.probe_stride = probe_stride; a.nprobe = nprobe; a.nprobe_q = nprobe_q;
   a.target_ids = target_ids; a.target_offsets = target_offsets; a.Lcap = L; a.k = topk;
   a.ids = ids; a.dist = dist; a.qmode = qmode; a.want_mode = want_mode;
-  const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
+  const size_t lds = table_bytes(M) + std::max<size_t>((size_t)kSelCap * 8, rot_m(M) ? (size_t)M * 1024 : 0);
   DISPATCH_M(M, { int rc = set_lds(k_ivf<MT>, lds); if (rc) return rc;
                   k_ivf<MT><<<Q, kScanThreads, lds, st>>>(a); });
   RII_HIP(hipGetLastError());
@@ -1456,29 +1630,38 @@ int rii_internal_sym_table(const rii_index* cidx, hipStream_t st) {
   return RII_OK;
 }
 
-int rii_assign(const rii_index_t* idx, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,
-               int32_t* assign_out, void* stream) {
-  if (!idx || n < 0 || K < 1 || !coarse || (n > 0 && (!codes || !assign_out))) return RII_ERR_INVALID_ARG;
+// a(n) by brute force.  rot_base >= 0: `codes` are stored rows rot_base .. rot_base+n-1 (rotated
+// storage when rot_m(M)); rot_base < 0: plain codes.
+int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base, const uint8_t* coarse,
+                        int K, int32_t* assign_out, hipStream_t st) {
   if (!m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
   if (n == 0) return RII_OK;
-  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!rot_m(idx->M)) rot_base = -1;
   int rc = rii_internal_sym_table(idx, st);
   if (rc) return rc;
   const int M = idx->M;
   const size_t lds = (size_t)M * 1024;
   int blocks = (int)std::min<int64_t>(n, 256 * 16);
   DISPATCH_M(M, { int rc2 = set_lds(k_assign<MT>, lds); if (rc2) return rc2;
-                  k_assign<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, M, coarse, K, assign_out); });
+                  k_assign<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, M, coarse, K, assign_out); });
   RII_HIP(hipGetLastError());
   return RII_OK;
 }
 
+int rii_assign(const rii_index_t* idx, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,
+               int32_t* assign_out, void* stream) {
+  if (!idx || n < 0 || K < 1 || !coarse || (n > 0 && (!codes || !assign_out))) return RII_ERR_INVALID_ARG;
+  return rii_internal_assign(idx, codes, n, -1, coarse, K, assign_out, static_cast<hipStream_t>(stream));
+}
+
 // a(n) with pruning (see k_assign_pruned); all pointers device.  visited_total may be NULL.
-int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, const uint8_t* super, int G,
+int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base,
+                               const uint8_t* super, int G,
                                const float* radius, const uint8_t* coarse_g, const int32_t* perm_g,
                                const int32_t* group_off, int32_t* assign_out, unsigned long long* visited_total,
                                hipStream_t st) {
   if (n == 0) return RII_OK;
+  if (!rot_m(idx->M)) rot_base = -1;
   int rc = rii_internal_sym_table(idx, st);
   if (rc) return rc;
   const int M = idx->M;
@@ -1486,27 +1669,28 @@ int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64
   if (lds > 150 * 1024) return RII_ERR_UNSUPPORTED;
   int blocks = (int)std::min<int64_t>(n, 256 * 32);
   DISPATCH_M(M, { int rc2 = set_lds(k_assign_pruned<MT>, lds); if (rc2) return rc2;
-                  k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, M, super, G, radius, coarse_g,
+                  k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, M, super, G, radius, coarse_g,
                                                                perm_g, group_off, assign_out, visited_total); });
   RII_HIP(hipGetLastError());
   return RII_OK;
 }
 
-// used by rii_index.hip
-int rii_internal_gather_rows(const uint8_t* codes, const int32_t* list_ids, int64_t N, int M, uint8_t* out,
-                             hipStream_t st) {
-  if (N == 0) return RII_OK;
+// used by rii_index.hip: see k_copy_rows.  The rotation arguments are ignored (plain) unless rot_m(M).
+int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, const int32_t* ids, int64_t n, int M, uint8_t* out,
+                           int64_t out_rot, hipStream_t st) {
+  if (n == 0) return RII_OK;
+  if (!rot_m(M)) in_rot = out_rot = -1;
   const int M4 = M / 4;
-  int64_t total = N * M4;
-  const int64_t per = (int64_t)1 << 30;
-  // one launch covers at most 2^30 dwords
-  for (int64_t r0 = 0; r0 < N; r0 += per / M4) {
-    int64_t cnt = std::min<int64_t>(per / M4, N - r0);
+  const int64_t per = ((int64_t)1 << 30) / M4;  // rows per launch
+  for (int64_t r0 = 0; r0 < n; r0 += per) {
+    int64_t cnt = std::min<int64_t>(per, n - r0);
     int64_t dw = cnt * M4;
-    k_gather_rows<<<(unsigned)((dw + 255) / 256), 256, 0, st>>>(codes, list_ids + r0, cnt, M4,
-                                                             reinterpret_cast<uint32_t*>(out) + r0 * M4);
+    // rows r0.. of this call: shift the rotation bases and (when not gathering) the source pointer
+    k_copy_rows<<<(unsigned)((dw + 255) / 256), 256, 0, st>>>(ids ? in : in + r0 * M,
+                                                           in_rot >= 0 && !ids ? in_rot + r0 : in_rot,
+                                                           ids ? ids + r0 : nullptr, cnt, M, out + r0 * M,
+                                                           out_rot >= 0 ? out_rot + r0 : out_rot);
   }
-  (void)total;
   RII_HIP(hipGetLastError());
   return RII_OK;
 }

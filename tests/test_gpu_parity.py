@@ -363,3 +363,35 @@ def test_pruned_assignment_equals_brute_force(rii, oracle_lib):
         assert np.array_equal(t2n(brute), a_ref)
         off_ref, lids_ref = oracle_lib.build_lists(a_ref, 1500)
         assert np.array_equal(off, off_ref) and np.array_equal(lids, lids_ref)
+
+
+def test_add_in_odd_pieces_and_read_back(rii, oracle_lib):
+    """Codes appended in pieces of odd length read back unchanged and score like one array
+    (the stored form of a row depends on its row number)."""
+    for M, D in ((8, 32), (16, 64), (32, 96), (12, 48)):
+        rng = np.random.default_rng(M)
+        cb = rng.normal(size=(M, 256, D // M)).astype(np.float32)
+        codes = rng.integers(0, 256, size=(9001, M)).astype(np.uint8)
+        index = rii.Index(cb)
+        cut = [0, 1, 38, 1000, 1003, 5000, 9001]
+        for a, b in zip(cut[:-1], cut[1:]):
+            if (a // 7) % 2:
+                index.add(torch.from_numpy(codes[a:b]).cuda())
+            else:
+                index.add(codes[a:b])
+        assert np.array_equal(index.get_codes(), codes)
+        assert np.array_equal(index.get_codes(37, 1970), codes[37:2007])
+        q = rng.normal(size=(3, D)).astype(np.float32)
+        lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+        ids, dist = rii.rii_adc_scan_linear(index, lut, 50)
+        tids = torch.arange(3, 9001, 7, dtype=torch.int32).cuda()
+        toff = torch.tensor([0, 0, 500, tids.numel()], dtype=torch.int64).cuda()
+        sub = rii.rii_adc_scan_subset(index, lut, tids, toff, tids.numel(), 50)
+        torch.cuda.synchronize()
+        A = oracle_lib.lut(cb, q)
+        for i in range(3):
+            ref = oracle_lib.linear_scan(A[i], codes, 50)
+            assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])
+            S = t2n(tids)[t2n(toff)[i]:t2n(toff)[i + 1]]
+            ref = oracle_lib.linear_scan(A[i], codes, 50, S=S)
+            assert np.array_equal(t2n(sub[0])[i], ref[0]) and np.array_equal(t2n(sub[1])[i], ref[1])
