@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the batched linear-scan kernel, from the rocprofv3 PMC runs summarised in
 # profiles/k_scan_w_c5_hbm_traffic_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated
 # with a plain streaming kernel).  Reported only for the exact configuration it was measured on.
-MEASURED_TRAFFIC = {("c5_billion_shard", 100_000_000, 10_000): 5_667_408_747 * 2.0 * 1024 + 44_005 * 1024}
+MEASURED_TRAFFIC = {("c5_billion_shard", 100_000_000, 10_000): 5_277_510_390 * 2.0 * 1024 + 56_996 * 1024}
 
 
 def log(*a):
