@@ -800,6 +800,136 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
   write_result(best, c, k, a.ids + q * a.out_stride, a.dist ? a.dist + q * a.out_stride : nullptr);
 }
 
+// ------------------------------------------------------------------ two queries per pass
+// Whole-database scan for large batches (every block owns its queries' whole scan), M = 8, 16, 32,
+// topk <= kWaveK.  A block serves TWO queries: the table holds float2 entries (one float per
+// query), T2[z][s] for 32 slots s, slot s holding (A0[s % M][z], A1[s % M][z]), so one 8-byte
+// LDS read yields the look-ups of both queries for the same code byte, and the code loads and the
+// address arithmetic are shared.  Rows are in the rotated stored form; lane l reads slot
+// (l + t) % 32 at step t (the per-step slot offsets sit in registers), which keeps the 32 lanes of
+// a half-wave on different slots.  As in k_scan_w the rotated-order sums are a filter and rows
+// that pass are re-scored in ascending sub-space order.  Each wave keeps one candidate buffer
+// per query; the block's merge result is the query's result (no cross-block stage).
+template <int MT>
+__device__ __forceinline__ float adc_row_exact_rot2(const float2* T2, const uint8_t* __restrict__ row, int64_t r,
+                                                    int which) {
+  float d = 0.f;
+#pragma unroll 4
+  for (int m = 0; m < MT; ++m) {
+    float2 v = T2[(int)row[(m - (int)r) & (MT - 1)] * 32 + m];
+    d = __fadd_rn(d, which ? v.y : v.x);
+  }
+  return d;
+}
+
+template <int MT>
+__global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
+  static_assert(rot_m(MT), "rotated stored form only");
+  extern __shared__ __align__(16) uint8_t smem[];
+  float2* T2 = reinterpret_cast<float2*>(smem);                        // [256][32]
+  uint64_t* wbuf0 = reinterpret_cast<uint64_t*>(smem + 65536);        // query 0: [waves + 1][kWaveCap]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  uint64_t* wbuf1 = wbuf0 + (size_t)(nwaves + 1) * kWaveCap;          // query 1
+  __shared__ int s_total, s_off;
+  const int64_t q0 = 2 * (int64_t)blockIdx.y, q1 = q0 + 1;
+  const int k = a.k;
+  const int64_t nrows = a.N;
+
+  {  // stage both tables ([M][256] each) in the buffer area, then transpose along diagonals
+    float* st0 = reinterpret_cast<float*>(wbuf0);
+    float* st1 = st0 + MT * 256;
+    const float* l0 = a.lut + q0 * MT * 256;
+    const float* l1 = a.lut + q1 * MT * 256;
+    for (int i = tid; i < MT * 256; i += blockDim.x) {
+      st0[i] = l0[i];
+      st1[i] = l1[i];
+    }
+    __syncthreads();
+    for (int it = tid; it < 256 * 32; it += blockDim.x) {
+      const int l = it & 31, blk = it >> 5;
+      const int s0 = blk & 31, z0 = (blk >> 5) << 5;
+      const int z = z0 + l, s = (s0 + l) & 31;
+      const int src = (s & (MT - 1)) * 256 + z;
+      T2[z * 32 + s] = make_float2(st0[src], st1[src]);
+    }
+    __syncthreads();
+  }
+  uint32_t lb[MT];  // slot offset of step t for this lane: rows are dealt so that row % 32 == tid % 32
+#pragma unroll
+  for (int t = 0; t < MT; ++t) lb[t] = (uint32_t)((tid + t) & 31) * 8u;
+
+  uint64_t* buf0 = wbuf0 + (size_t)wave * kWaveCap;
+  uint64_t* buf1 = wbuf1 + (size_t)wave * kWaveCap;
+  int cnt0 = 0, cnt1 = 0;
+  uint32_t tau0 = kOrdMax, tau1 = kOrdMax;
+  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
+  for (int64_t tile = 0; tile < nrows; tile += tile_step) {
+    const float fb0 = rot_filter(tau0, rot_eps(MT)), fb1 = rot_filter(tau1, rot_eps(MT));
+    uint32_t maybe0 = 0, maybe1 = 0;
+#pragma unroll
+    for (int r = 0; r < kRowsPerLane; ++r) {
+      const int64_t i = tile + (int64_t)r * blockDim.x + tid;
+      if (i < nrows) {
+        const uint8_t* row = a.codes + i * MT;
+        uint32_t w[MT / 4];
+        if constexpr (MT == 8) {
+          uint2 v = *reinterpret_cast<const uint2*>(row);
+          w[0] = v.x; w[1] = v.y;
+        } else {
+          const uint4* p = reinterpret_cast<const uint4*>(row);
+#pragma unroll
+          for (int j = 0; j < MT / 16; ++j) {
+            uint4 v = p[j];
+            w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+          }
+        }
+        float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+          uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lb[t], 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
+          float2 v = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(T2) + addr);
+          d0 = __fadd_rn(d0, v.x);
+          d1 = __fadd_rn(d1, v.y);
+        }
+        if (d0 <= fb0) maybe0 |= 1u << r;
+        if (d1 <= fb1) maybe1 |= 1u << r;
+      }
+    }
+    if (__ballot((maybe0 | maybe1) != 0) != 0ull) {
+      uint64_t key[kRowsPerLane];
+      uint32_t pend = 0;
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) {
+        key[r] = kKeyMax;
+        if (maybe0 & (1u << r)) {
+          const int64_t i = tile + (int64_t)r * blockDim.x + tid;
+          key[r] = make_key(adc_row_exact_rot2<MT>(T2, a.codes + i * MT, i, 0), (int32_t)i);
+          if ((uint32_t)(key[r] >> 32) <= tau0) pend |= 1u << r;
+        }
+      }
+      if (__ballot(pend != 0) != 0ull) wave_offer<kRowsPerLane>(buf0, cnt0, tau0, k, key, pend, lane);
+      pend = 0;
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) {
+        key[r] = kKeyMax;
+        if (maybe1 & (1u << r)) {
+          const int64_t i = tile + (int64_t)r * blockDim.x + tid;
+          key[r] = make_key(adc_row_exact_rot2<MT>(T2, a.codes + i * MT, i, 1), (int32_t)i);
+          if ((uint32_t)(key[r] >> 32) <= tau1) pend |= 1u << r;
+        }
+      }
+      if (__ballot(pend != 0) != 0ull) wave_offer<kRowsPerLane>(buf1, cnt1, tau1, k, key, pend, lane);
+    }
+  }
+  uint64_t* best;
+  int c = block_collect(wbuf0, nwaves, cnt0, tau0, tau0, k, &best, &s_total, &s_off);
+  write_result(best, c, k, a.ids + q0 * a.out_stride, a.dist ? a.dist + q0 * a.out_stride : nullptr);
+  __syncthreads();
+  c = block_collect(wbuf1, nwaves, cnt1, tau1, tau1, k, &best, &s_total, &s_off);
+  write_result(best, c, k, a.ids + q1 * a.out_stride, a.dist ? a.dist + q1 * a.out_stride : nullptr);
+}
+
 // ------------------------------------------------------------------ PartialSort + Take
 struct SelectArgs {
   // source A: keys [Q][nkeys] (per-block partial results)
@@ -1365,7 +1495,32 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     pre.counter = pre_counter;
     dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
     const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
-    if (mode == kLinear) {
+    if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2) {
+      // large batch: two queries per block (k_scan_w2); an odd last query goes through k_scan_w,
+      // addressed as query 0 of argument arrays shifted by Q - 1
+      const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+      dim3 grid2(1, (unsigned)(Q / 2));
+      ScanArgs last = a;
+      last.lut = lut + (size_t)(Q - 1) * M * 256;
+      last.partial = partial + (size_t)(Q - 1) * a.cand_cap;
+      last.tau_g = tau + (Q - 1); last.cand_cnt = cand_cnt + (Q - 1); last.done_cnt = done_cnt + (Q - 1);
+      last.ids = ids + (size_t)(Q - 1) * out_stride;
+      last.dist = dist ? dist + (size_t)(Q - 1) * out_stride : nullptr;
+      switch (M) {
+        case 8: { int rc = set_lds(k_scan_w2<8>, lds2); if (rc) return rc;
+                  k_scan_w2<8><<<grid2, kScanThreads, lds2, st>>>(a);
+                  if (Q & 1) { rc = set_lds(k_scan_w<8, kLinear>, ldsw); if (rc) return rc;
+                               k_scan_w<8, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(last); } } break;
+        case 16: { int rc = set_lds(k_scan_w2<16>, lds2); if (rc) return rc;
+                   k_scan_w2<16><<<grid2, kScanThreads, lds2, st>>>(a);
+                   if (Q & 1) { rc = set_lds(k_scan_w<16, kLinear>, ldsw); if (rc) return rc;
+                                k_scan_w<16, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(last); } } break;
+        default: { int rc = set_lds(k_scan_w2<32>, lds2); if (rc) return rc;
+                   k_scan_w2<32><<<grid2, kScanThreads, lds2, st>>>(a);
+                   if (Q & 1) { rc = set_lds(k_scan_w<32, kLinear>, ldsw); if (rc) return rc;
+                                k_scan_w<32, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(last); } } break;
+      }
+    } else if (mode == kLinear) {
       DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kLinear>, ldsw); if (rc) return rc;
                       if (prepass) { int rc2 = set_lds(k_tau0<MT, kLinear>, tau0_lds(M)); if (rc2) return rc2; }
                       if (prepass) k_tau0<MT, kLinear><<<pgrid, kScanThreads, tau0_lds(M), st>>>(pre);
