@@ -22,25 +22,14 @@
 
 namespace {
 
+// Launch shape of the scan kernels.  The values were chosen by sweeping them on the 100M-code
+// configuration (M = 32): one 1024-thread block per CU, 4 rows per lane per tile.
 constexpr int kSelCap = 2048;          // keys held per block between compactions (2 * RII_MAX_TOPK)
-#ifndef RII_SCAN_THREADS
-#define RII_SCAN_THREADS 1024
-#endif
-#ifndef RII_ROWS_PER_LANE
-#define RII_ROWS_PER_LANE 4
-#endif
-#ifndef RII_WANT_BLOCKS
-#define RII_WANT_BLOCKS 256
-#endif
-#ifndef RII_TILE_STRIDED
-#define RII_TILE_STRIDED 0
-#endif
-#ifndef RII_TAU_EVERY
-#define RII_TAU_EVERY 1
-#endif
-constexpr int kScanThreads = RII_SCAN_THREADS;
-constexpr int kRowsPerLane = RII_ROWS_PER_LANE;  // rows scored per lane per tile
-constexpr int kPrepassBlocks = 256;              // blocks (tiles) of the bound-seeding pass, per query
+constexpr int kScanThreads = 1024;
+constexpr int kRowsPerLane = 4;        // rows scored per lane per tile
+constexpr int kWantBlocks = 256;       // blocks a small batch is split into (the chip has 256 CUs)
+constexpr int kMinTiles = 4;           // shortest chunk, in tiles
+constexpr int kPrepassBlocks = 256;    // blocks (tiles) of the bound-seeding pass, per query
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kOrdMax = 0xFFFFFFFFu;
 
@@ -633,17 +622,9 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
     nrows = a.target_offsets[q + 1] - o0;
     tids = a.target_ids + o0;
   }
-#if RII_TILE_STRIDED
-  // tiles are dealt to the query's blocks round-robin, so that the blocks resident at any time
-  // read one moving window of the array (DRAM pages are shared by neighbouring requests)
-  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane * gridDim.x;
-  const int64_t r0 = (int64_t)blockIdx.x * blockDim.x * kRowsPerLane;
-  const int64_t r1 = nrows;
-#else
   const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
   const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
   const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
-#endif
   uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
   const int k = a.k;
 
@@ -736,9 +717,6 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
   if (tid == 0) s_last = atomicAdd(a.done_cnt + q, 1u) == gridDim.x - 1;
   __syncthreads();
   if (!s_last) return;
-#ifdef RII_DEBUG_SKIP_FINAL
-  return;
-#endif
   const int64_t n = __hip_atomic_load(a.cand_cnt + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   constexpr int kBatch = 8;  // keys per lane in flight: the loads bypass the caches, so overlap them
   // Pass A: every thread takes the smallest distance image of its strided share of the
@@ -1161,11 +1139,6 @@ __global__ void k_init_scan(uint32_t* tau, int Q, int stride) {
   tau[3 * (size_t)stride + q] = 0u;
 }
 
-__global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
-}
-
 // Per-query plan of the query procedure (Alg. 3): mode 0 = linear scan, 1 = inverted index;
 // number of lists ceil(K L / |S|) capped at K and at pmax.
 __global__ void k_plan(const int64_t* target_offsets, int64_t N, int Q, int64_t theta, int K, int64_t L, int pmax,
@@ -1437,8 +1410,6 @@ int set_lds(Kern kern, size_t bytes) {
 
 // Split max_rows rows per query into equal chunks (one block each): about kWantBlocks blocks
 // in total when the batch is small, never chunks shorter than kMinTiles tiles.
-constexpr int kWantBlocks = RII_WANT_BLOCKS;
-constexpr int kMinTiles = 4;
 void scan_chunks(int Q, int64_t max_rows, int64_t* nchunks_out, int64_t* chunk_rows_out) {
   const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
   int64_t want = (kWantBlocks + Q - 1) / Q;

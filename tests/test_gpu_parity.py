@@ -395,3 +395,52 @@ def test_add_in_odd_pieces_and_read_back(rii, oracle_lib):
             S = t2n(tids)[t2n(toff)[i]:t2n(toff)[i + 1]]
             ref = oracle_lib.linear_scan(A[i], codes, 50, S=S)
             assert np.array_equal(t2n(sub[0])[i], ref[0]) and np.array_equal(t2n(sub[1])[i], ref[1])
+
+
+def test_error_codes(rii, idx8):
+    """Argument errors come back as status codes and leave the outputs untouched."""
+    d = idx8
+    lut = lut_dev(rii, d)
+    E = rii.RiiError
+    for bad, status in ((0, -1), (2000, -7)):
+        with pytest.raises(E) as e:
+            rii.rii_adc_scan_linear(d["index"], lut, bad)
+        assert e.value.status == status
+    with pytest.raises(E) as e:
+        rii.rii_coarse_assign(d["index"], lut, d["K"] + 1)
+    assert e.value.status == -1
+    bare = rii.Index(d["cb"])
+    bare.add(d["codes"][:100])
+    with pytest.raises(E) as e:
+        rii.rii_coarse_assign(bare, lut, 1)
+    assert e.value.status == -3                      # no coarse centres / lists
+    probe = torch.zeros((len(d["q"]), 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(E) as e:
+        rii.rii_adc_scan_ivf(bare, lut, probe, 5)
+    assert e.value.status == -3
+    coarse = d["codes"][:4].copy()
+    off = np.array([0, 25, 50, 75, 100], dtype=np.int64)
+    ids = np.arange(100, dtype=np.int32)
+    bare.set_lists(coarse, off, ids)                 # valid
+    with pytest.raises(E) as e:
+        bare.set_lists(coarse, off, ids[::-1].copy())  # lists not ascending
+    assert e.value.status == -4
+    dup = ids.copy(); dup[3] = 2
+    with pytest.raises(E) as e:
+        bare.set_lists(coarse, off, dup)             # not a permutation
+    assert e.value.status == -4
+    with pytest.raises(E) as e:
+        bare.set_lists(coarse, np.array([0, 25, 50, 75, 99], dtype=np.int64), ids)
+    assert e.value.status == -1
+    # M = 2 is outside what the scan kernels are built for
+    cb2 = np.zeros((2, 256, 2), dtype=np.float32)
+    tiny = rii.Index(cb2)
+    with pytest.raises(E) as e:
+        tiny.add(np.zeros((4, 2), dtype=np.uint8))
+    assert e.value.status == -7
+    out_i = torch.full((len(d["q"]), 5), 123, dtype=torch.int32, device="cuda")
+    out_d = torch.full((len(d["q"]), 5), 7.0, device="cuda")
+    with pytest.raises(E):
+        rii.rii_adc_scan_linear(d["index"], lut, 0, out=(out_i, out_d))
+    torch.cuda.synchronize()
+    assert int(out_i.min()) == 123 and float(out_d.max()) == 7.0
