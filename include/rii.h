@@ -118,6 +118,18 @@ int rii_index_reconfigure(rii_index_t* index, int K, int iters, uint64_t seed);
 /* The threshold theta of Alg. 3 (default 0: always the inverted index when lists exist). */
 int rii_index_set_threshold(rii_index_t* index, int64_t theta);
 
+/* Choose theta by measurement (Sec. 4.2, "Selection": the threshold is found by running both
+ * search methods for several settings when the structure is built and fitting a line).  For
+ * target-set sizes |S| = 64, 256, ... up to max_targets (0 = N) this times, on the GPU and for a
+ * batch of nq queries (decoded stored codes, seeded choice), the linear scan over S and the
+ * inverted index with ceil(K L / |S|) lists, candidate cap L and the target filter; theta is the
+ * crossing point of the two timing curves (straight lines in log-log between the bracketing
+ * sizes), 0 if the inverted index is never slower, max_targets + 1 if it is never faster.  The
+ * value is stored in the index and returned in *theta_out (may be NULL).  It depends on the
+ * batch size nq the caller intends to use.  Needs posting lists.  Synchronous. */
+int rii_index_calibrate_threshold(rii_index_t* index, int64_t L, int topk, int nq, int64_t max_targets,
+                                  uint64_t seed, int64_t* theta_out);
+
 /* Measurement aid: while two hipEvent_t (passed as void*) are set, every rii_adc_scan_linear
  * call (and the linear-scan branch of rii_query) records `start_event` right before and
  * `stop_event` right after the kernel that streams the code array (Alg. 1, the loop over s),

@@ -167,6 +167,14 @@ class Index:
     def set_threshold(self, theta: int):
         _check(self._lib.rii_index_set_threshold(self._h, i64(theta)), "rii_index_set_threshold")
 
+    def calibrate_threshold(self, L: int, topk: int = 100, nq: int = 64, max_targets: int = 0, seed: int = 0) -> int:
+        """Measure the linear-scan / inverted-index crossover and store it as theta."""
+        theta = ctypes.c_int64(0)
+        _check(self._lib.rii_index_calibrate_threshold(self._h, i64(L), topk, nq, i64(max_targets),
+                                                       ctypes.c_uint64(seed), ctypes.byref(theta)),
+               "rii_index_calibrate_threshold")
+        return int(theta.value)
+
     def info(self) -> dict:
         out = np.zeros(8, dtype=np.int64)
         _check(self._lib.rii_index_info(self._h, _hp(out)), "rii_index_info")

@@ -20,6 +20,7 @@ extern "C" int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* c
                                           const uint8_t* super, int G, const float* radius, const uint8_t* coarse_g,
                                           const int32_t* perm_g, const int32_t* group_off, int32_t* assign_out,
                                           unsigned long long* visited_total, hipStream_t st);
+extern "C" int rii_internal_spread_ids(int32_t* ids, int64_t* offsets, int nq, int64_t S, int64_t N, hipStream_t st);
 extern "C" int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, const int32_t* ids, int64_t n, int M,
                                       uint8_t* out, int64_t out_rot, hipStream_t st);
 
@@ -202,6 +203,45 @@ int assign_stored(rii_index* idx, int64_t first, int64_t n, const uint8_t* coars
   return rc;
 }
 
+// helpers of the threshold calibration
+
+struct DevBuf {
+  void* p = nullptr;
+  ~DevBuf() {
+    if (p) (void)hipFree(p);
+  }
+  int alloc(size_t bytes) {
+    if (hipMalloc(&p, bytes ? bytes : 16) == hipSuccess) return RII_OK;
+    (void)hipGetLastError();
+    return RII_ERR_OOM;
+  }
+  template <typename T>
+  T* as() { return static_cast<T*>(p); }
+};
+
+// median of three timed runs of f() in milliseconds (f launches on the default stream)
+template <typename F>
+int time_ms(F f, double* out) {
+  hipEvent_t a, b;
+  RII_HIP(hipEventCreate(&a));
+  RII_HIP(hipEventCreate(&b));
+  float t[3] = {0.f, 0.f, 0.f};
+  int rc = f();  // warm-up (also sizes the scratch)
+  for (int i = 0; i < 3 && !rc; ++i) {
+    RII_HIP(hipEventRecord(a, nullptr));
+    rc = f();
+    RII_HIP(hipEventRecord(b, nullptr));
+    RII_HIP(hipEventSynchronize(b));
+    RII_HIP(hipEventElapsedTime(&t[i], a, b));
+  }
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (rc) return rc;
+  std::sort(t, t + 3);
+  *out = t[1];
+  return RII_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -225,6 +265,7 @@ int rii_index_create(const float* codebooks, int D, int M, int Ks, rii_index_t**
     rii_index_destroy(idx);
     return RII_ERR_DEVICE;
   }
+  idx->h_cb.assign(codebooks, codebooks + (size_t)M * Ks * idx->Ds);
   *out = idx;
   return RII_OK;
 }
@@ -249,6 +290,89 @@ int rii_index_set_scan_events(rii_index_t* idx, void* start_event, void* stop_ev
   if (!idx || ((start_event == nullptr) != (stop_event == nullptr))) return RII_ERR_INVALID_ARG;
   idx->ev_start = start_event;
   idx->ev_stop = stop_event;
+  return RII_OK;
+}
+
+// ---- threshold calibration (Sec. 4.2, "Selection")
+int rii_index_calibrate_threshold(rii_index_t* idx, int64_t L, int topk, int nq, int64_t max_targets, uint64_t seed,
+                                  int64_t* theta_out) {
+  if (!idx || L < 1 || topk < 1 || topk > RII_MAX_TOPK || nq < 1 || nq > 1024) return RII_ERR_INVALID_ARG;
+  if (idx->K < 1) return RII_ERR_NOT_BUILT;
+  if (idx->N < 2 || idx->h_cb.size() != (size_t)idx->M * 256 * idx->Ds) return RII_ERR_INVALID_ARG;
+  const int64_t N = idx->N;
+  const int M = idx->M, D = idx->D, Ds = idx->Ds, K = idx->K;
+  if (max_targets <= 0 || max_targets > N) max_targets = N;
+  // queries: decoded stored codes (vectors the index can certainly answer), seeded choice
+  std::vector<int64_t> rows = rii_host::sample_without_replacement(N, std::min<int64_t>(nq, N), seed);
+  std::vector<float> q((size_t)nq * D);
+  {
+    std::vector<uint8_t> code(M);
+    for (int i = 0; i < nq; ++i) {
+      int rc = rii_index_get_codes(idx, rows[i % rows.size()], 1, code.data(), RII_MEM_HOST);
+      if (rc) return rc;
+      for (int m = 0; m < M; ++m)
+        std::memcpy(&q[(size_t)i * D + m * Ds], &idx->h_cb[((size_t)m * 256 + code[m]) * Ds], sizeof(float) * Ds);
+    }
+  }
+  std::vector<int64_t> sizes;
+  for (int64_t s = 64; s < max_targets; s *= 4) sizes.push_back(s);
+  sizes.push_back(max_targets);
+  DevBuf d_q, d_lut, d_tid, d_off, d_probe, d_ids, d_dist;
+  int rc = d_q.alloc((size_t)nq * D * 4);
+  if (!rc) rc = d_lut.alloc((size_t)nq * M * 256 * 4);
+  if (!rc) rc = d_tid.alloc((size_t)nq * max_targets * 4);
+  if (!rc) rc = d_off.alloc((size_t)(nq + 1) * 8);
+  if (!rc) rc = d_probe.alloc((size_t)nq * K * 4);
+  if (!rc) rc = d_ids.alloc((size_t)nq * topk * 4);
+  if (!rc) rc = d_dist.alloc((size_t)nq * topk * 4);
+  if (rc) return rc;
+  RII_HIP(hipMemcpy(d_q.p, q.data(), q.size() * 4, hipMemcpyHostToDevice));
+  rc = rii_build_lut(idx, d_q.as<float>(), nq, d_lut.as<float>(), nullptr);
+  if (rc) return rc;
+  // time both branches of Alg. 3 on every size
+  std::vector<double> t_lin(sizes.size()), t_ivf(sizes.size());
+  for (size_t g = 0; g < sizes.size(); ++g) {
+    const int64_t S = sizes[g];
+    rc = rii_internal_spread_ids(d_tid.as<int32_t>(), d_off.as<int64_t>(), nq, S, N, nullptr);
+    if (rc) return rc;
+    int64_t p64 = ((int64_t)K * L + S - 1) / S;
+    const int P = (int)std::min<int64_t>(std::max<int64_t>(p64, 1), K);
+    if (P > RII_MAX_TOPK && K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
+    rc = time_ms([&] {
+      return rii_adc_scan_subset(idx, d_lut.as<float>(), nq, d_tid.as<int32_t>(), d_off.as<int64_t>(), S, topk,
+                                 d_ids.as<int32_t>(), d_dist.as<float>(), nullptr);
+    }, &t_lin[g]);
+    if (rc) return rc;
+    rc = time_ms([&] {
+      int r2 = rii_coarse_assign(idx, d_lut.as<float>(), nq, P, d_probe.as<int32_t>(), nullptr, nullptr);
+      if (r2) return r2;
+      return rii_adc_scan_ivf(idx, d_lut.as<float>(), nq, d_probe.as<int32_t>(), P, d_tid.as<int32_t>(),
+                              d_off.as<int64_t>(), L, topk, d_ids.as<int32_t>(), d_dist.as<float>(), nullptr);
+    }, &t_ivf[g]);
+    if (rc) return rc;
+  }
+  // theta = the size from which the inverted index is the faster branch: the crossing point of
+  // the two timing curves, each taken as a straight line in (log |S|, log t) between the two
+  // grid sizes that bracket the crossing
+  int64_t theta;
+  size_t g = 0;
+  while (g < sizes.size() && t_ivf[g] > t_lin[g]) ++g;
+  if (g == 0) {
+    theta = 0;                       // the inverted index wins everywhere
+  } else if (g == sizes.size()) {
+    theta = max_targets + 1;         // the linear scan wins on the whole grid
+  } else {
+    const double x0 = std::log((double)sizes[g - 1]), x1 = std::log((double)sizes[g]);
+    const double a0 = std::log(t_lin[g - 1]) - std::log(t_ivf[g - 1]);  // > 0: linear scan faster... sign below
+    const double a1 = std::log(t_lin[g]) - std::log(t_ivf[g]);
+    // difference d(x) = log t_lin - log t_ivf is negative at x0 (linear faster) and >= 0 at x1
+    double x = a1 == a0 ? x1 : x0 + (0.0 - a0) * (x1 - x0) / (a1 - a0);
+    if (x < x0) x = x0;
+    if (x > x1) x = x1;
+    theta = (int64_t)std::llround(std::exp(x));
+  }
+  idx->theta = theta;
+  if (theta_out) *theta_out = theta;
   return RII_OK;
 }
 

@@ -17,6 +17,7 @@ struct rii_index {
   int64_t theta = 0;     // switch threshold of the query procedure
 
   float* d_cb = nullptr;          // [M][256][Ds] codebooks
+  std::vector<float> h_cb;        // host mirror of the codebooks
   float* d_sym = nullptr;         // [M][256][256] code-word-to-code-word squared distances (lazy)
   // "Stored" code arrays (d_codes, d_codes_list, d_coarse_st) keep row r rotated by r bytes when
   // M is 8, 16 or 32 (stored[r][t] = code[r][(t + r) % M]), plain otherwise; see rii_kernels.hip.

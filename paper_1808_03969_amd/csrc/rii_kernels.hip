@@ -1164,6 +1164,18 @@ __global__ void k_iota_offsets(int64_t* off, int Q, int64_t len) {
   if (i <= Q) off[i] = (int64_t)i * len;
 }
 
+// Evenly spread, strictly increasing target identifiers for the threshold calibration:
+// query i gets ids[i * S + j] = floor((j + i / nq) * N / S), j < S; offsets[i] = i * S.
+__global__ void k_spread_ids(int32_t* ids, int64_t* offsets, int nq, int64_t S, int64_t N) {
+  int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g <= nq) offsets[g] = g * S;
+  if (g >= (int64_t)nq * S) return;
+  int64_t i = g / S, j = g - i * S;
+  double pos = ((double)j + (double)i / (double)nq) * ((double)N / (double)S);
+  int64_t v = (int64_t)pos;
+  ids[g] = (int32_t)(v < N ? v : N - 1);
+}
+
 // ------------------------------------------------------------------ offline kernels
 // Eq. (1): grid (ceil(n / 256), M), block 256; thread = one vector, block = one sub-space.
 __global__ void k_encode(const float* __restrict__ cb, const float* __restrict__ x, int64_t n, int D, int M, int Ds,
@@ -1797,6 +1809,14 @@ int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64
   DISPATCH_M(M, { int rc2 = set_lds(k_assign_pruned<MT>, lds); if (rc2) return rc2;
                   k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, M, super, G, radius, coarse_g,
                                                                perm_g, group_off, assign_out, visited_total); });
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+// used by the threshold calibration in rii_index.hip
+int rii_internal_spread_ids(int32_t* ids, int64_t* offsets, int nq, int64_t S, int64_t N, hipStream_t st) {
+  int64_t total = std::max<int64_t>((int64_t)nq * S, nq + 1);
+  k_spread_ids<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(ids, offsets, nq, S, N);
   RII_HIP(hipGetLastError());
   return RII_OK;
 }

@@ -444,3 +444,25 @@ def test_error_codes(rii, idx8):
         rii.rii_adc_scan_linear(d["index"], lut, 0, out=(out_i, out_d))
     torch.cuda.synchronize()
     assert int(out_i.min()) == 123 and float(out_d.max()) == 7.0
+
+
+def test_threshold_calibration(rii, oracle_lib, idx16):
+    """theta is measured on the GPU; whatever value comes out, Alg. 3 with it equals the oracle's."""
+    d = idx16
+    N, K, R = d["N"], d["K"], 50
+    L = N // K
+    theta = d["index"].calibrate_threshold(L, topk=R, nq=16, seed=3)
+    assert 0 <= theta <= N + 1 and d["index"].info()["theta"] == theta
+    assert d["index"].calibrate_threshold(L, topk=R, nq=16, max_targets=4096, seed=3) <= 4097
+    d["index"].set_threshold(theta)
+    Q = len(d["q"])
+    sizes = [max(1, min(N, int(theta * f))) for f in (0.25, 0.5, 0.9, 1.0, 1.1, 2.0, 4.0)] + [N // 3] * (Q - 7)
+    tids, toff = synth.subset_batch(80, N, sizes)
+    ids, dist = rii.rii_query(d["index"], d["q_dev"], R, tids.cuda(), toff.cuda(), max(sizes), L)
+    torch.cuda.synchronize()
+    tids, toff = t2n(tids), t2n(toff)
+    for i in range(Q):
+        ref = oracle_lib.query(d["cb"], d["q"][i], d["codes"], d["coarse"], d["off"], d["lids"], R, L, theta,
+                               S=tids[toff[i]:toff[i + 1]])
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    d["index"].set_threshold(0)
