@@ -598,6 +598,94 @@ __device__ int block_collect(uint64_t* wbuf, int nwaves, int cnt, uint32_t tau, 
   return *s_total;
 }
 
+// Append the block's c best keys (sorted, at best[0..c)) to the query's candidate list and, when
+// the block holds k of them, tighten the query's shared bound.  Block-wide.
+__device__ void publish_block_result(const uint64_t* best, int c, int k, uint64_t* cand, uint32_t* cand_cnt,
+                                     uint32_t* tau_g, int* s_off) {
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    *s_off = c ? (int)atomicAdd(cand_cnt, (uint32_t)c) : 0;
+    if (c >= k) atomicMin(tau_g, (uint32_t)(best[k - 1] >> 32));
+  }
+  __syncthreads();
+  for (int i = tid; i < c; i += blockDim.x)
+    __hip_atomic_store(cand + (uint32_t)*s_off + i, best[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Every block of a query calls this once after publishing.  The block that arrives last (ticket
+// counter) selects the query's k best from the candidate list and writes the result.
+// wbuf = [nwaves + 1][kWaveCap] keys of LDS, free for use.
+__device__ void finish_query(uint64_t* wbuf, int nwaves, int k, const uint64_t* cand, const uint32_t* cand_cnt,
+                             uint32_t* done_cnt, unsigned nblocks, int32_t* ids, float* dist, int* s_total,
+                             int* s_off, int* s_last) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
+  wait_own_memory_ops();
+  __syncthreads();
+  if (tid == 0) *s_last = atomicAdd(done_cnt, 1u) == nblocks - 1;
+  __syncthreads();
+  if (!*s_last) return;
+  const int64_t n = __hip_atomic_load(cand_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  constexpr int kBatch = 8;  // keys per lane in flight: the loads bypass the caches, so overlap them
+  // Pass A: every thread takes the smallest distance image of its strided share of the
+  // candidates; the k-th smallest of these per-thread minima (k different candidates) bounds
+  // the k-th smallest candidate, and about k candidates lie below it.
+  uint32_t tau = kOrdMax;
+  if (n > kWaveCap) {
+    uint32_t mine = kOrdMax;
+    for (int64_t i0 = 0; i0 < n; i0 += (int64_t)blockDim.x * kBatch) {
+      uint64_t key[kBatch];
+#pragma unroll
+      for (int r = 0; r < kBatch; ++r) {
+        const int64_t i = i0 + (int64_t)r * blockDim.x + tid;
+        key[r] = i < n ? __hip_atomic_load(cand + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kKeyMax;
+      }
+#pragma unroll
+      for (int r = 0; r < kBatch; ++r) {
+        uint32_t o = (uint32_t)(key[r] >> 32);
+        if (o < mine) mine = o;
+      }
+    }
+    uint32_t* s_min = reinterpret_cast<uint32_t*>(wbuf);  // [blockDim.x]
+    s_min[tid] = mine;
+    __syncthreads();
+    if ((int)blockDim.x >= k) {  // every wave finds the same value: no broadcast needed
+      uint32_t v[kScanThreads / 64];
+#pragma unroll
+      for (int j = 0; j < kScanThreads / 64; ++j) v[j] = s_min[lane + 64 * j];
+      uint32_t ans = 0;
+      for (int b = 31; b >= 0; --b) {
+        const uint32_t trial = ans | (1u << b);
+        int c = 0;
+#pragma unroll
+        for (int j = 0; j < kScanThreads / 64; ++j) c += v[j] < trial;
+        for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+        if (c < k) ans = trial;
+      }
+      tau = ans;
+    }
+    __syncthreads();
+  }
+  // Pass B: keep what is not above the bound (per-wave buffers as in the scan), then merge.
+  int cnt = 0;
+  for (int64_t i0 = (int64_t)wave * 64 * kBatch; i0 < n; i0 += (int64_t)nwaves * 64 * kBatch) {
+    uint64_t key[kBatch];
+    uint32_t pend = 0;
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r) {
+      const int64_t i = i0 + r * 64 + lane;
+      key[r] = i < n ? __hip_atomic_load(cand + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kKeyMax;
+    }
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r)
+      if (key[r] != kKeyMax && (uint32_t)(key[r] >> 32) <= tau) pend |= 1u << r;
+    if (__ballot(pend != 0) != 0ull) wave_offer<kBatch>(buf, cnt, tau, k, key, pend, lane);
+  }
+  uint64_t* best;
+  const int c = block_collect(wbuf, nwaves, cnt, tau, kOrdMax, k, &best, s_total, s_off);
+  write_result(best, c, k, ids, dist);
+}
+
 template <int MT, int MODE>
 __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
   extern __shared__ __align__(16) uint8_t smem[];
@@ -702,80 +790,10 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
     const uint32_t bound = tg < tau ? tg : tau;
     uint64_t* best;
     const int c = block_collect(wbuf, nwaves, cnt, tau, bound, k, &best, &s_total, &s_off);
-    if (tid == 0) {
-      s_off = c ? (int)atomicAdd(a.cand_cnt + q, (uint32_t)c) : 0;
-      if (c >= k) atomicMin(a.tau_g + q, (uint32_t)(best[k - 1] >> 32));
-    }
-    __syncthreads();
-    for (int i = tid; i < c; i += blockDim.x)
-      __hip_atomic_store(cand + (uint32_t)s_off + i, best[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
   }
-
-  // ---- the block that finishes last selects the query's result from the candidate list
-  wait_own_memory_ops();
-  __syncthreads();
-  if (tid == 0) s_last = atomicAdd(a.done_cnt + q, 1u) == gridDim.x - 1;
-  __syncthreads();
-  if (!s_last) return;
-  const int64_t n = __hip_atomic_load(a.cand_cnt + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  constexpr int kBatch = 8;  // keys per lane in flight: the loads bypass the caches, so overlap them
-  // Pass A: every thread takes the smallest distance image of its strided share of the
-  // candidates; the k-th smallest of these per-thread minima (k different candidates) bounds
-  // the k-th smallest candidate, and about k candidates lie below it.
-  uint32_t tau = kOrdMax;
-  if (n > kWaveCap) {
-    uint32_t mine = kOrdMax;
-    for (int64_t i0 = 0; i0 < n; i0 += (int64_t)blockDim.x * kBatch) {
-      uint64_t key[kBatch];
-#pragma unroll
-      for (int r = 0; r < kBatch; ++r) {
-        const int64_t i = i0 + (int64_t)r * blockDim.x + tid;
-        key[r] = i < n ? __hip_atomic_load(cand + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kKeyMax;
-      }
-#pragma unroll
-      for (int r = 0; r < kBatch; ++r) {
-        uint32_t o = (uint32_t)(key[r] >> 32);
-        if (o < mine) mine = o;
-      }
-    }
-    uint32_t* s_min = reinterpret_cast<uint32_t*>(wbuf);  // [blockDim.x]
-    s_min[tid] = mine;
-    __syncthreads();
-    if ((int)blockDim.x >= k) {  // every wave finds the same value: no broadcast needed
-      uint32_t v[kScanThreads / 64];
-#pragma unroll
-      for (int j = 0; j < kScanThreads / 64; ++j) v[j] = s_min[lane + 64 * j];
-      uint32_t ans = 0;
-      for (int b = 31; b >= 0; --b) {
-        const uint32_t trial = ans | (1u << b);
-        int c = 0;
-#pragma unroll
-        for (int j = 0; j < kScanThreads / 64; ++j) c += v[j] < trial;
-        for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
-        if (c < k) ans = trial;
-      }
-      tau = ans;
-    }
-    __syncthreads();
-  }
-  // Pass B: keep what is not above the bound (per-wave buffers as in the scan), then merge.
-  int cnt = 0;
-  for (int64_t i0 = (int64_t)wave * 64 * kBatch; i0 < n; i0 += (int64_t)nwaves * 64 * kBatch) {
-    uint64_t key[kBatch];
-    uint32_t pend = 0;
-#pragma unroll
-    for (int r = 0; r < kBatch; ++r) {
-      const int64_t i = i0 + r * 64 + lane;
-      key[r] = i < n ? __hip_atomic_load(cand + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kKeyMax;
-    }
-#pragma unroll
-    for (int r = 0; r < kBatch; ++r)
-      if (key[r] != kKeyMax && (uint32_t)(key[r] >> 32) <= tau) pend |= 1u << r;
-    if (__ballot(pend != 0) != 0ull) wave_offer<kBatch>(buf, cnt, tau, k, key, pend, lane);
-  }
-  uint64_t* best;
-  const int c = block_collect(wbuf, nwaves, cnt, tau, kOrdMax, k, &best, &s_total, &s_off);
-  write_result(best, c, k, a.ids + q * a.out_stride, a.dist ? a.dist + q * a.out_stride : nullptr);
+  finish_query(wbuf, nwaves, k, cand, a.cand_cnt + q, a.done_cnt + q, gridDim.x, a.ids + q * a.out_stride,
+               a.dist ? a.dist + q * a.out_stride : nullptr, &s_total, &s_off, &s_last);
 }
 
 // ------------------------------------------------------------------ two queries per pass
@@ -1027,6 +1045,12 @@ struct IvfArgs {
   float* dist;
   const int* qmode;
   int want_mode;
+  // multi-block variant (k_ivf_w): per-query shared bound, candidate list and counters
+  uint32_t* tau_g;
+  uint32_t* cand_cnt;
+  uint32_t* done_cnt;
+  uint64_t* cand;
+  int64_t cand_cap;
 };
 
 __device__ __forceinline__ bool is_member(const int32_t* S, int64_t nS, int32_t n) {
@@ -1126,6 +1150,84 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
   __syncthreads();
   sel_compact(keys, &s_cnt, &s_tau, a.k);
   write_result(keys, s_cnt, a.k, a.ids + q * a.k, a.dist ? a.dist + q * a.k : nullptr);
+}
+
+// Inverted-index scan without a candidate cap, split over several blocks per query: block b of
+// a query takes the probed lists b, b + gridDim.x, ... (the result of Alg. 2 does not depend on
+// the visiting order when all members of the probed lists are scored).  Selection per wavefront
+// as in k_scan_w; the blocks' results meet in the query's candidate list.
+template <int MT>
+__global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int M = MT ? MT : a.M;
+  float* A = reinterpret_cast<float*>(smem);
+  uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + table_bytes(M));  // [waves + 1][kWaveCap]
+  __shared__ int s_total, s_off, s_last;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  const int64_t q = blockIdx.y;
+  uint64_t* cand = a.cand + q * a.cand_cap;
+  const int k = a.k;
+  const int np = a.nprobe;
+  if ((int)blockIdx.x < np) {  // block-uniform: this block has at least one list
+    if constexpr (rot_m(MT)) {
+      fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), a.lut + q * M * 256);
+    } else {
+      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = a.lut[q * M * 256 + i];
+      __syncthreads();
+    }
+    const int32_t* S = nullptr;
+    int64_t nS = 0;
+    if (a.target_ids) {
+      int64_t o0 = a.target_offsets[q];
+      S = a.target_ids + o0;
+      nS = a.target_offsets[q + 1] - o0;
+    }
+    uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
+    int cnt = 0;
+    uint32_t tau = kOrdMax;
+    for (int p = blockIdx.x; p < np; p += gridDim.x) {
+      const int list = a.probe[q * a.probe_stride + p];
+      const int64_t b = a.list_off[list], e = a.list_off[list + 1];
+      const uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int64_t t0 = b; t0 < e; t0 += (int64_t)blockDim.x * kRowsPerLane) {
+        const uint32_t bound = tg < tau ? tg : tau;
+        const float fb = rot_filter(bound, rot_eps(M));
+        uint64_t key[kRowsPerLane];
+        uint32_t pend = 0;
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          const int64_t pos = t0 + (int64_t)r * blockDim.x + tid;
+          key[r] = kKeyMax;
+          if (pos < e) {
+            const int32_t id = a.list_ids[pos];
+            if (S && !is_member(S, nS, id)) continue;
+            float d;
+            if constexpr (rot_m(MT)) {
+              d = adc_row_rot<MT>(A, a.codes_list + pos * M, ((uint32_t)pos & 31u) << 2);
+              if (!(d <= fb)) continue;
+              d = adc_row_exact_rot<MT>(A, a.codes_list + pos * M, pos);
+            } else {
+              d = adc_row<MT>(A, a.codes_list + pos * M, M);
+            }
+            key[r] = make_key(d, id);
+            if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
+          }
+        }
+        if (__ballot(pend != 0) != 0ull) {
+          const uint32_t before = tau;
+          wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
+          if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
+        }
+      }
+    }
+    const uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint64_t* best;
+    const int c = block_collect(wbuf, nwaves, cnt, tau, tg < tau ? tg : tau, k, &best, &s_total, &s_off);
+    publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
+  }
+  finish_query(wbuf, nwaves, k, cand, a.cand_cnt + q, a.done_cnt + q, gridDim.x, a.ids + q * a.k,
+               a.dist ? a.dist + q * a.k : nullptr, &s_total, &s_off, &s_last);
 }
 
 // ------------------------------------------------------------------ small utility kernels
@@ -1647,9 +1749,20 @@ int rii_coarse_assign(const rii_index_t* idx, const float* lut, int Q, int nprob
                      static_cast<hipStream_t>(stream));
 }
 
+// Blocks per query of the multi-block inverted-index scan.
+static int ivf_split(int Q, int nprobe) {
+  int split = (kWantBlocks + Q - 1) / Q;
+  if (split > nprobe) split = nprobe;
+  return split < 1 ? 1 : split;
+}
+
+static size_t ivf_ws_bytes(int Q, int nprobe, int topk) {
+  return 4 * align_up((size_t)Q * 4, 256) + (size_t)Q * ivf_split(Q, nprobe) * topk * 8 + 256;
+}
+
 static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32_t* probe, int probe_stride,
                       int nprobe, const int* nprobe_q, const int32_t* target_ids, const int64_t* target_offsets,
-                      int64_t L, int topk, int32_t* ids, float* dist, const int* qmode, int want_mode,
+                      int64_t L, int topk, int32_t* ids, float* dist, const int* qmode, int want_mode, void* ws,
                       hipStream_t st) {
   const int M = idx->M;
   IvfArgs a{};
@@ -1657,6 +1770,22 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
   a.lut = lut; a.probe = probe; a.probe_stride = probe_stride; a.nprobe = nprobe; a.nprobe_q = nprobe_q;
   a.target_ids = target_ids; a.target_offsets = target_offsets; a.Lcap = L; a.k = topk;
   a.ids = ids; a.dist = dist; a.qmode = qmode; a.want_mode = want_mode;
+  if (L == 0 && topk <= kWaveK && !nprobe_q && !qmode && ws && Q <= 65535) {
+    // no candidate cap: any visiting order gives the same result, so split the lists over blocks
+    const int split = ivf_split(Q, nprobe);
+    const size_t cstride = align_up((size_t)Q * 4, 256) / 4;
+    uint32_t* tau = static_cast<uint32_t*>(ws);
+    a.tau_g = tau; a.cand_cnt = tau + cstride; a.done_cnt = tau + 3 * cstride;
+    a.cand = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(ws) + 4 * cstride * 4);
+    a.cand_cap = (int64_t)split * topk;
+    k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
+    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+    dim3 grid((unsigned)split, (unsigned)Q);
+    DISPATCH_M(M, { int rc = set_lds(k_ivf_w<MT>, ldsw); if (rc) return rc;
+                    k_ivf_w<MT><<<grid, kScanThreads, ldsw, st>>>(a); });
+    RII_HIP(hipGetLastError());
+    return RII_OK;
+  }
   const size_t lds = table_bytes(M) + std::max<size_t>((size_t)kSelCap * 8, rot_m(M) ? (size_t)M * 1024 : 0);
   DISPATCH_M(M, { int rc = set_lds(k_ivf<MT>, lds); if (rc) return rc;
                   k_ivf<MT><<<Q, kScanThreads, lds, st>>>(a); });
@@ -1672,8 +1801,14 @@ int rii_adc_scan_ivf(const rii_index_t* idx, const float* lut, int Q, const int3
   if (nprobe < 1 || nprobe > idx->K) return RII_ERR_INVALID_ARG;
   if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
   if (topk > RII_MAX_TOPK || !m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
+  void* ws = nullptr;
+  if (L == 0 && topk <= kWaveK) {
+    int rc = ensure_ws(idx, ivf_ws_bytes(Q, nprobe, topk));
+    if (rc) return rc;
+    ws = idx->ws;
+  }
   return launch_ivf(idx, lut, Q, probe_lists, nprobe, nprobe, nullptr, target_ids, target_offsets, L, topk, ids,
-                    dist, nullptr, 0, static_cast<hipStream_t>(stream));
+                    dist, nullptr, 0, ws, static_cast<hipStream_t>(stream));
 }
 
 int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int32_t* target_ids,
@@ -1732,7 +1867,7 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
     rc = coarse_rank(idx, lut, Q, pmax, probe, nullptr, pmax, qmode, 1, stage_ws, st);
     if (rc) return rc;
     rc = launch_ivf(idx, lut, Q, probe, pmax, pmax, nprobe_q, target_ids, target_offsets, L, topk, ids, dist, qmode,
-                    1, st);
+                    1, nullptr, st);
     if (rc) return rc;
   }
   RII_HIP(hipGetLastError());
