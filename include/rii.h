@@ -217,6 +217,13 @@ int rii_query(const rii_index_t* index, const float* q, int Q, int topk, const i
  *   x device [n][D] fp32; codes_out device [n][M] uint8 (written). */
 int rii_encode_device(const rii_index_t* index, const float* x, int64_t n, uint8_t* codes_out, void* stream);
 
+/* Rotation of the OPQ variant (Sec. 4.5): y = R x for every row, applied to database vectors
+ * before rii_encode_device and to queries before rii_build_lut / rii_query; everything after it
+ * is plain PQ.  The matrix is pre-trained elsewhere.  fp32, inner index ascending, no fused
+ * multiply-add (bit-identical on host and GPU, because the result feeds the arg-min of Eq. (1)).
+ *   R device [D][D] row-major; x device [n][D]; y device [n][D] (written; must not alias x). */
+int rii_rotate(const float* R, int D, const float* x, int64_t n, float* y, void* stream);
+
 /* a(n) of Sec. 4.1 for arbitrary codes under explicit coarse centres.
  *   codes device [n][M]; coarse device [K][M]; assign_out device [n] int32 (written). */
 int rii_assign(const rii_index_t* index, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,

@@ -203,3 +203,14 @@ def build_lists(a, K):
 
 def index_bytes(N, K, M):
     return int(lib().orc_index_bytes(ctypes.c_int64(N), ctypes.c_int64(K), ctypes.c_int64(M)))
+
+
+def rotate(R, x):
+    """Sec. 4.5: y = R x for every row of x (fp32, fixed summation order)."""
+    R, x = _f32(R), _f32(np.atleast_2d(x))
+    n, D = x.shape
+    if R.shape != (D, D):
+        raise ValueError("rotation must be D x D")
+    out = np.empty((n, D), dtype=np.float32)
+    _check(lib().orc_rotate(_p(R), D, _p(x), ctypes.c_int64(n), _p(out)), "rotate")
+    return out

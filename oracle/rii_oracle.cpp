@@ -13,6 +13,7 @@
 //   * Query             Sec. 4.2, Alg. 3 (|S| < theta -> linear scan, else inverted index).
 //   * a(n), W_k         Sec. 4.1, Eq. (4): nearest coarse centre under the symmetric distance.
 //   * memory model      Sec. 4.1: (N+K) M log2 Z + 32 N bits.
+//   * rotation          Sec. 4.5: y = R x before encoding / table building (OPQ variant).
 //
 // Readings where the paper is silent (all listed in the design document): identifiers are
 // 0-based; ties are broken towards the lower index (code word, list number, identifier);
@@ -292,6 +293,23 @@ int orc_build_lists(const int32_t* assign, int64_t N, int K, int64_t* list_off, 
   for (int k = 0; k < K; ++k) list_off[k + 1] = list_off[k] + count[k + 1];
   std::vector<int64_t> cursor(list_off, list_off + K);
   for (int64_t n = 0; n < N; ++n) list_ids[cursor[assign[n]]++] = (int32_t)n;
+  return 0;
+}
+
+// Sec. 4.5 (OPQ variant): the input vector is first rotated with a pre-trained D x D matrix,
+// y = R x; everything after that is plain PQ.  fp32, inner index ascending, no fused
+// multiply-add (the rotated vector feeds the arg-min of Eq. (1), so the precision is fixed).
+// R [D][D] row-major, x [n][D], y_out [n][D].
+int orc_rotate(const float* R, int D, const float* x, int64_t n, float* y_out) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int r = 0; r < D; ++r) {
+      float acc = 0.f;
+      for (int c = 0; c < D; ++c) {
+        float prod = R[(size_t)r * D + c] * x[i * D + c];
+        acc = acc + prod;
+      }
+      y_out[i * D + r] = acc;
+    }
   return 0;
 }
 

@@ -291,6 +291,17 @@ def rii_encode_device(index: Index, x: torch.Tensor, out: torch.Tensor | None = 
     return codes
 
 
+def rii_rotate(R: torch.Tensor, x: torch.Tensor) -> torch.Tensor:
+    """y = R x per row (the rotation of the OPQ variant, Sec. 4.5)."""
+    n, D = x.shape
+    if R.shape != (D, D):
+        raise ValueError("rotation must be D x D")
+    y = torch.empty_like(x)
+    _check(load_library().rii_rotate(_dp(R, torch.float32), D, _dp(x, torch.float32), i64(n), _dp(y, torch.float32),
+                                     _stream()), "rii_rotate")
+    return y
+
+
 def rii_assign(index: Index, codes: torch.Tensor, coarse: torch.Tensor) -> torch.Tensor:
     n, K = codes.shape[0], coarse.shape[0]
     out = torch.empty(n, dtype=torch.int32, device=codes.device)

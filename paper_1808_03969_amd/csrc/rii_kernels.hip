@@ -1308,6 +1308,31 @@ __global__ void k_encode(const float* __restrict__ cb, const float* __restrict__
   codes[row * M + m] = (uint8_t)best;
 }
 
+// Sec. 4.5 (OPQ variant): y = R x per row.  Block = 32 output coordinates x 8 rows; the inner
+// index runs in ascending order through 32-wide LDS tiles with one accumulator per output, one
+// rounding per operation, so the result is bit-identical to the plain triple loop.
+__global__ __launch_bounds__(256) void k_rotate(const float* __restrict__ R, int D, const float* __restrict__ x,
+                                                int64_t n, float* __restrict__ y) {
+  __shared__ float Rs[32][33];
+  __shared__ float Xs[8][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r = blockIdx.x * 32 + tx;
+  const int64_t i = (int64_t)blockIdx.y * 8 + ty;
+  float acc = 0.f;
+  for (int c0 = 0; c0 < D; c0 += 32) {
+    for (int rr = ty; rr < 32; rr += 8) {
+      int gr = blockIdx.x * 32 + rr, gc = c0 + tx;
+      Rs[rr][tx] = (gr < D && gc < D) ? R[(size_t)gr * D + gc] : 0.f;
+    }
+    Xs[ty][tx] = (i < n && c0 + tx < D) ? x[i * D + c0 + tx] : 0.f;
+    __syncthreads();
+    const int cmax = D - c0 < 32 ? D - c0 : 32;
+    for (int c = 0; c < cmax; ++c) acc = __fadd_rn(acc, __fmul_rn(Rs[tx][c], Xs[ty][c]));
+    __syncthreads();
+  }
+  if (r < D && i < n) y[i * D + r] = acc;
+}
+
 // Symmetric table: sym[m][i][j] = squared distance between code words i and j of codebook m.
 // grid (256, M), block 256.
 __global__ void k_sym_table(const float* __restrict__ cb, int Ds, float* __restrict__ sym) {
@@ -1888,6 +1913,20 @@ int rii_encode_device(const rii_index_t* idx, const float* x, int64_t n, uint8_t
     int64_t cnt = std::min(max_rows, n - r0);
     dim3 grid((unsigned)((cnt + 255) / 256), (unsigned)idx->M);
     k_encode<<<grid, 256, lds, st>>>(idx->d_cb, x + r0 * idx->D, cnt, idx->D, idx->M, Ds, codes_out + r0 * idx->M);
+  }
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_rotate(const float* R, int D, const float* x, int64_t n, float* y, void* stream) {
+  if (!R || D < 1 || n < 0 || (n > 0 && (!x || !y)) || x == y) return RII_ERR_INVALID_ARG;
+  if (n == 0) return RII_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t rows_per_launch = (int64_t)65535 * 8;
+  for (int64_t r0 = 0; r0 < n; r0 += rows_per_launch) {
+    int64_t cnt = std::min(rows_per_launch, n - r0);
+    dim3 grid((unsigned)((D + 31) / 32), (unsigned)((cnt + 7) / 8));
+    k_rotate<<<grid, 256, 0, st>>>(R, D, x + r0 * D, cnt, y + r0 * D);
   }
   RII_HIP(hipGetLastError());
   return RII_OK;

@@ -466,3 +466,37 @@ def test_threshold_calibration(rii, oracle_lib, idx16):
                                S=tids[toff[i]:toff[i + 1]])
         check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
     d["index"].set_threshold(0)
+
+
+def test_rotation_opq_variant(rii, oracle_lib):
+    """Sec. 4.5: rotate, then plain PQ.  The rotation is bit-identical to the oracle's, and the
+    whole rotated pipeline (encode, table, scan) matches the oracle run on the rotated inputs."""
+    rng = np.random.default_rng(4)
+    for D in (24, 96, 130):
+        Rm, _ = np.linalg.qr(rng.normal(size=(D, D)))
+        Rm = Rm.astype(np.float32)
+        x = rng.normal(size=(1003, D)).astype(np.float32)
+        y = rii.rii_rotate(torch.from_numpy(Rm).cuda(), torch.from_numpy(x).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(t2n(y), oracle_lib.rotate(Rm, x))
+    D, M, N = 96, 16, 20000
+    Rm, _ = np.linalg.qr(rng.normal(size=(D, D)))
+    Rm = Rm.astype(np.float32)
+    x = t2n(synth.mixture(31, 0, N, D))
+    q = t2n(synth.mixture(32, 0, 6, D, means_seed=31))
+    Rd = torch.from_numpy(Rm).cuda()
+    xr = rii.rii_rotate(Rd, torch.from_numpy(x).cuda())
+    qr = rii.rii_rotate(Rd, torch.from_numpy(q).cuda())
+    cb = rii.rii_train_codebooks(t2n(xr)[:4000], M, iters=3, seed=1)
+    index = rii.Index(cb)
+    codes = rii.rii_encode_device(index, xr)
+    index.add(codes)
+    ids, dist = rii.rii_adc_scan_linear(index, rii.rii_build_lut(index, qr), 30)
+    torch.cuda.synchronize()
+    xr_ref, qr_ref = oracle_lib.rotate(Rm, x), oracle_lib.rotate(Rm, q)
+    codes_ref = oracle_lib.encode(cb, xr_ref)
+    assert np.array_equal(t2n(codes), codes_ref)
+    A = oracle_lib.lut(cb, qr_ref)
+    for i in range(6):
+        ref = oracle_lib.linear_scan(A[i], codes_ref, 30)
+        assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])

@@ -329,3 +329,29 @@ def test_oracle_cost_scales_with_subset_size(oracle_lib):
             t0 = time.perf_counter(); oracle_lib.linear_scan(A, codes, 10, S=S); best = min(best, time.perf_counter() - t0)
         return best
     assert t(320000) > 4 * t(20000)
+
+
+# ---------------------------------------------------------------- rotation (Sec. 4.5)
+def test_rotation(oracle_lib):
+    """y = R x: identity leaves x alone; a permutation matrix permutes coordinates exactly; an
+    orthogonal R preserves norms and distances (so PQ after rotating data and query alike is the
+    method of Sec. 4.5); agrees with numpy's matmul in float64."""
+    rng = np.random.default_rng(2)
+    D = 24
+    x = rng.normal(size=(50, D)).astype(np.float32)
+    assert np.array_equal(oracle_lib.rotate(np.eye(D, dtype=np.float32), x), x)
+    perm = rng.permutation(D)
+    P = np.zeros((D, D), dtype=np.float32)
+    P[np.arange(D), perm] = 1.0
+    assert np.array_equal(oracle_lib.rotate(P, x), x[:, perm])
+    Rm, _ = np.linalg.qr(rng.normal(size=(D, D)))
+    y = oracle_lib.rotate(Rm.astype(np.float32), x)
+    np.testing.assert_allclose(y, x.astype(np.float64) @ Rm.T, rtol=1e-5, atol=1e-5)
+    np.testing.assert_allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-5)
+    dx = ((x[:, None, :] - x[None, :, :]) ** 2).sum(2)
+    dy = ((y[:, None, :] - y[None, :, :]) ** 2).sum(2)
+    np.testing.assert_allclose(dy, dx, rtol=1e-4, atol=1e-4)
+    # not symmetric in R: a transposed operand would fail here
+    A = rng.normal(size=(D, D)).astype(np.float32)
+    e0 = np.zeros((1, D), dtype=np.float32); e0[0, 0] = 1.0
+    assert np.array_equal(oracle_lib.rotate(A, e0)[0], A[:, 0])
