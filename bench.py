@@ -165,7 +165,7 @@ def main():
     alg_bytes = float(Q) * N * M          # M bytes per code and query pass
     achieved = alg_bytes / (scan_avg_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": f"k_scan_w<{M},linear>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "bound": "hbm", "kernel": f"k_scan_w4<{M}> (batched launch) / k_scan_w<{M},linear> (single query)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_TRAFFIC.get((cfg.name, N, Q)),
         "launch_ms": round(scan_avg_ms, 3), "algorithmic_bytes_per_launch": alg_bytes,

@@ -12,6 +12,7 @@
 // identifier) order, so selection is exact and deterministic including ties.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 
 #include <algorithm>
 #include <cstdio>
@@ -413,15 +414,16 @@ __device__ __forceinline__ void wave_compact(uint64_t* buf, int& cnt, uint32_t& 
   }
 }
 
+// `cap` = keys the wave's buffer holds (kWaveCap unless the kernel says otherwise; must exceed k).
 template <int R>
 __device__ __forceinline__ void wave_offer(uint64_t* buf, int& cnt, uint32_t& tau, int k, const uint64_t (&key)[R],
-                                           uint32_t pend, int lane) {
+                                           uint32_t pend, int lane, int cap = kWaveCap) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     bool p = ((pend >> r) & 1u) && (uint32_t)(key[r] >> 32) <= tau;
     unsigned long long m;
     while ((m = __ballot(p)) != 0ull) {
-      const int room = kWaveCap - cnt;
+      const int room = cap - cnt;
       const int rank = __popcll(m & ((1ull << lane) - 1ull));
       const int n = __popcll(m);
       if (p && rank < room) {
@@ -429,7 +431,7 @@ __device__ __forceinline__ void wave_offer(uint64_t* buf, int& cnt, uint32_t& ta
         p = false;
       }
       cnt += n < room ? n : room;
-      if (cnt == kWaveCap) {
+      if (cnt == cap) {
         wave_sync();
         wave_compact(buf, cnt, tau, k, lane);
         p = p && (uint32_t)(key[r] >> 32) <= tau;
@@ -526,12 +528,12 @@ __global__ __launch_bounds__(kScanThreads) void k_tau0(ScanArgs a) {
 
 // The waves of a block hold cnt keys each in their buffers.  Leaves the block's k smallest keys
 // (of those not above `bound`), sorted ascending, at (*out)[0..c) and returns c.  Block-wide;
-// ends with a barrier.  wbuf = [nwaves][kWaveCap] wave buffers followed by one more kWaveCap keys.
+// ends with a barrier.  wbuf = [nwaves][cap] wave buffers followed by one more cap keys.
 __device__ int block_collect(uint64_t* wbuf, int nwaves, int cnt, uint32_t tau, uint32_t bound, int k,
-                             uint64_t** out, int* s_total, int* s_off) {
+                             uint64_t** out, int* s_total, int* s_off, int cap = kWaveCap) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
-  uint64_t* small = wbuf + (size_t)nwaves * kWaveCap;
+  uint64_t* buf = wbuf + (size_t)wave * cap;
+  uint64_t* small = wbuf + (size_t)nwaves * cap;
   if (tid == 0) {
     *s_total = 0;
     *s_off = 0;
@@ -548,7 +550,7 @@ __device__ int block_collect(uint64_t* wbuf, int nwaves, int cnt, uint32_t tau, 
   if (lane == 0 && nsurv) atomicAdd(s_total, nsurv);
   __syncthreads();
   const int total = *s_total;
-  if (total <= kWaveCap) {
+  if (total <= cap) {
     int base = 0;
     if (lane == 0 && nsurv) base = atomicAdd(s_off, nsurv);
     base = __shfl(base, 0, 64);
@@ -924,6 +926,166 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
   __syncthreads();
   c = block_collect(wbuf1, nwaves, cnt1, tau1, tau1, k, &best, &s_total, &s_off);
   write_result(best, c, k, a.ids + q1 * a.out_stride, a.dist ? a.dist + q1 * a.out_stride : nullptr);
+}
+
+// ------------------------------------------------------------------ four queries per pass
+// Same setting as k_scan_w2 (whole-database scan, large batch, M = 8, 16, 32), four queries per
+// block, with the table held in half precision: T4[z][s] for 32 slots, each entry four fp16 values
+// (one per query), so one 8-byte LDS read serves four look-ups, and the sums are formed with
+// packed fp16 additions.  The fp16 sum is only a FILTER.  Per query the table is scaled by a
+// power of two so that no sum can overflow; with h = fp16(a) per entry and fp16 additions the
+// computed sum is at most  S (1 + 2^-11)^M + 2 M 2^-25  for an exact (scaled) sum S, so a row whose
+// exact distance is within the bound always satisfies
+//     fp16 sum <= bound * scale * (1 + 1.1 M 2^-11) + M 2^-23 .
+// Rows that pass are re-scored from the fp32 table in global memory, in ascending sub-space
+// order; results are therefore exactly those of the fp32 kernels.  Each wave keeps one candidate
+// buffer of kWaveCap4 keys per query.
+constexpr int kWaveCap4 = 128;
+constexpr int kWaveK4 = 100;  // largest topk this kernel takes (must stay below kWaveCap4)
+
+// ascending-m fp32 sum for stored row r (rotated form), table A = lut[M][256] in global memory
+template <int MT>
+__device__ __forceinline__ float adc_row_unrot_global(const float* __restrict__ A, const uint8_t* __restrict__ row,
+                                                      int64_t r) {
+  float d = 0.f;
+#pragma unroll 4
+  for (int m = 0; m < MT; ++m) d = __fadd_rn(d, A[m * 256 + row[(m - (int)r) & (MT - 1)]]);
+  return d;
+}
+
+template <int MT>
+__global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
+  static_assert(rot_m(MT), "rotated stored form only");
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint2* T4 = reinterpret_cast<uint2*>(smem);                          // [256][32] x 4 halves
+  uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + 65536);          // [4][waves + 1][kWaveCap4]
+  __shared__ float s_red[kScanThreads / 64];
+  __shared__ float s_scale[4];
+  __shared__ int s_total, s_off;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  const size_t qstride = (size_t)(nwaves + 1) * kWaveCap4;
+  const int64_t q0 = 4 * (int64_t)blockIdx.y;
+  const int k = a.k;
+  const int64_t nrows = a.N;
+
+  // tables: one query at a time through a staging copy (the buffer area), scaled, rounded to
+  // fp16 and written along diagonals (see fill_table_rot)
+  {
+    float* stage = reinterpret_cast<float*>(wbuf);
+    __half* T4h = reinterpret_cast<__half*>(smem);
+    for (int j = 0; j < 4; ++j) {
+      const float* lut = a.lut + (q0 + j) * MT * 256;
+      float mx = 0.f;
+      for (int i = tid; i < MT * 256; i += blockDim.x) {
+        float v = lut[i];
+        stage[i] = v;
+        mx = fmaxf(mx, v);
+      }
+      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+      if (lane == 0) s_red[wave] = mx;
+      __syncthreads();
+      if (tid == 0) {
+        float m2 = 0.f;
+        for (int w = 0; w < nwaves; ++w) m2 = fmaxf(m2, s_red[w]);
+        // largest power of two with MT * max * scale <= 16384 (no fp16 sum can reach 65504)
+        int e = 0;
+        if (m2 > 0.f) {
+          (void)frexpf(m2 * (float)MT, &e);  // m2 * MT = f * 2^e, f in [0.5, 1)
+          e = 14 - e;
+        }
+        if (e > 24) e = 24;    // keep tiny tables out of the fp32 exponent's far end
+        if (e < -120) e = -120;
+        s_scale[j] = ldexpf(1.f, e);
+      }
+      __syncthreads();
+      const float sc = s_scale[j];
+      for (int it = tid; it < 256 * 32; it += blockDim.x) {
+        const int l = it & 31, blk = it >> 5;
+        const int s0 = blk & 31, z0 = (blk >> 5) << 5;
+        const int z = z0 + l, s = (s0 + l) & 31;
+        T4h[(size_t)(z * 32 + s) * 4 + j] = __float2half_rn(stage[(s & (MT - 1)) * 256 + z] * sc);
+      }
+      __syncthreads();
+    }
+  }
+  uint32_t lb[MT];  // slot offset of step t for this lane: rows are dealt so that row % 32 == tid % 32
+#pragma unroll
+  for (int t = 0; t < MT; ++t) lb[t] = (uint32_t)((tid + t) & 31) * 8u;
+  const float scale0 = s_scale[0], scale1 = s_scale[1], scale2 = s_scale[2], scale3 = s_scale[3];
+  const float rel = 1.f + 1.1f * (float)MT * 4.8828125e-4f;   // 1 + 1.1 M 2^-11
+  const float slack = (float)MT * 1.1920929e-7f;               // M 2^-23
+
+  int cnt[4] = {0, 0, 0, 0};
+  uint32_t tau[4] = {kOrdMax, kOrdMax, kOrdMax, kOrdMax};
+  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
+  for (int64_t tile = 0; tile < nrows; tile += tile_step) {
+    float fb[4];
+    const float scl[4] = {scale0, scale1, scale2, scale3};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      fb[j] = tau[j] == kOrdMax ? __uint_as_float(0x7F800000u) : float_of_ord(tau[j]) * scl[j] * rel + slack;
+    uint32_t maybe[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < kRowsPerLane; ++r) {
+      const int64_t i = tile + (int64_t)r * blockDim.x + tid;
+      if (i < nrows) {
+        const uint8_t* row = a.codes + i * MT;
+        uint32_t w[MT / 4];
+        if constexpr (MT == 8) {
+          uint2 v = *reinterpret_cast<const uint2*>(row);
+          w[0] = v.x; w[1] = v.y;
+        } else {
+          const uint4* p = reinterpret_cast<const uint4*>(row);
+#pragma unroll
+          for (int jj = 0; jj < MT / 16; ++jj) {
+            uint4 v = p[jj];
+            w[4 * jj] = v.x; w[4 * jj + 1] = v.y; w[4 * jj + 2] = v.z; w[4 * jj + 3] = v.w;
+          }
+        }
+        __half2 acc01 = __float2half2_rn(0.f), acc23 = __float2half2_rn(0.f);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+          uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lb[t], 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
+          uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(T4) + addr);
+          acc01 = __hadd2(acc01, *reinterpret_cast<const __half2*>(&v.x));
+          acc23 = __hadd2(acc23, *reinterpret_cast<const __half2*>(&v.y));
+        }
+        if (__low2float(acc01) <= fb[0]) maybe[0] |= 1u << r;
+        if (__high2float(acc01) <= fb[1]) maybe[1] |= 1u << r;
+        if (__low2float(acc23) <= fb[2]) maybe[2] |= 1u << r;
+        if (__high2float(acc23) <= fb[3]) maybe[3] |= 1u << r;
+      }
+    }
+    if (__ballot((maybe[0] | maybe[1] | maybe[2] | maybe[3]) != 0) != 0ull) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (__ballot(maybe[j] != 0) == 0ull) continue;  // wave-uniform
+        const float* A = a.lut + (q0 + j) * MT * 256;
+        uint64_t key[kRowsPerLane];
+        uint32_t pend = 0;
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          key[r] = kKeyMax;
+          if (maybe[j] & (1u << r)) {
+            const int64_t i = tile + (int64_t)r * blockDim.x + tid;
+            key[r] = make_key(adc_row_unrot_global<MT>(A, a.codes + i * MT, i), (int32_t)i);
+            if ((uint32_t)(key[r] >> 32) <= tau[j]) pend |= 1u << r;
+          }
+        }
+        if (__ballot(pend != 0) != 0ull)
+          wave_offer<kRowsPerLane>(wbuf + j * qstride + (size_t)wave * kWaveCap4, cnt[j], tau[j], k, key, pend, lane,
+                                   kWaveCap4);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint64_t* best;
+    int c = block_collect(wbuf + j * qstride, nwaves, cnt[j], tau[j], tau[j], k, &best, &s_total, &s_off, kWaveCap4);
+    write_result(best, c, k, a.ids + (q0 + j) * a.out_stride, a.dist ? a.dist + (q0 + j) * a.out_stride : nullptr);
+    __syncthreads();
+  }
 }
 
 // ------------------------------------------------------------------ PartialSort + Take
@@ -1606,29 +1768,57 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
     const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
     if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2) {
-      // large batch: two queries per block (k_scan_w2); an odd last query goes through k_scan_w,
-      // addressed as query 0 of argument arrays shifted by Q - 1
+      // Large batch, every block owns its queries' whole scan: four queries per block with the
+      // half-precision filter (k_scan_w4) when topk allows, then two per block (k_scan_w2) and a
+      // single one (k_scan_w) for what is left.  Later groups are addressed as query 0.. of
+      // argument arrays shifted by the number of queries already launched.
+      auto shifted = [&](int o) {
+        ScanArgs b = a;
+        b.lut = lut + (size_t)o * M * 256;
+        b.partial = partial + (size_t)o * a.cand_cap;
+        b.tau_g = tau + o; b.cand_cnt = cand_cnt + o; b.done_cnt = done_cnt + o;
+        b.ids = ids + (size_t)o * out_stride;
+        b.dist = dist ? dist + (size_t)o * out_stride : nullptr;
+        return b;
+      };
+      const size_t lds4 = 65536 + 4 * (size_t)(kScanThreads / 64 + 1) * kWaveCap4 * 8;
       const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
-      dim3 grid2(1, (unsigned)(Q / 2));
-      ScanArgs last = a;
-      last.lut = lut + (size_t)(Q - 1) * M * 256;
-      last.partial = partial + (size_t)(Q - 1) * a.cand_cap;
-      last.tau_g = tau + (Q - 1); last.cand_cnt = cand_cnt + (Q - 1); last.done_cnt = done_cnt + (Q - 1);
-      last.ids = ids + (size_t)(Q - 1) * out_stride;
-      last.dist = dist ? dist + (size_t)(Q - 1) * out_stride : nullptr;
-      switch (M) {
-        case 8: { int rc = set_lds(k_scan_w2<8>, lds2); if (rc) return rc;
-                  k_scan_w2<8><<<grid2, kScanThreads, lds2, st>>>(a);
-                  if (Q & 1) { rc = set_lds(k_scan_w<8, kLinear>, ldsw); if (rc) return rc;
-                               k_scan_w<8, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(last); } } break;
-        case 16: { int rc = set_lds(k_scan_w2<16>, lds2); if (rc) return rc;
-                   k_scan_w2<16><<<grid2, kScanThreads, lds2, st>>>(a);
-                   if (Q & 1) { rc = set_lds(k_scan_w<16, kLinear>, ldsw); if (rc) return rc;
-                                k_scan_w<16, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(last); } } break;
-        default: { int rc = set_lds(k_scan_w2<32>, lds2); if (rc) return rc;
-                   k_scan_w2<32><<<grid2, kScanThreads, lds2, st>>>(a);
-                   if (Q & 1) { rc = set_lds(k_scan_w<32, kLinear>, ldsw); if (rc) return rc;
-                                k_scan_w<32, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(last); } } break;
+      int done = 0;
+      if (topk <= kWaveK4 && Q >= 4) {
+        dim3 g4(1, (unsigned)(Q / 4));
+        switch (M) {
+          case 8: { int rc = set_lds(k_scan_w4<8>, lds4); if (rc) return rc;
+                    k_scan_w4<8><<<g4, kScanThreads, lds4, st>>>(a); } break;
+          case 16: { int rc = set_lds(k_scan_w4<16>, lds4); if (rc) return rc;
+                     k_scan_w4<16><<<g4, kScanThreads, lds4, st>>>(a); } break;
+          default: { int rc = set_lds(k_scan_w4<32>, lds4); if (rc) return rc;
+                     k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a); } break;
+        }
+        done = Q / 4 * 4;
+      }
+      if (Q - done >= 2) {
+        ScanArgs b = shifted(done);
+        dim3 g2(1, (unsigned)((Q - done) / 2));
+        switch (M) {
+          case 8: { int rc = set_lds(k_scan_w2<8>, lds2); if (rc) return rc;
+                    k_scan_w2<8><<<g2, kScanThreads, lds2, st>>>(b); } break;
+          case 16: { int rc = set_lds(k_scan_w2<16>, lds2); if (rc) return rc;
+                     k_scan_w2<16><<<g2, kScanThreads, lds2, st>>>(b); } break;
+          default: { int rc = set_lds(k_scan_w2<32>, lds2); if (rc) return rc;
+                     k_scan_w2<32><<<g2, kScanThreads, lds2, st>>>(b); } break;
+        }
+        done += (Q - done) / 2 * 2;
+      }
+      if (Q - done == 1) {
+        ScanArgs b = shifted(done);
+        switch (M) {
+          case 8: { int rc = set_lds(k_scan_w<8, kLinear>, ldsw); if (rc) return rc;
+                    k_scan_w<8, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
+          case 16: { int rc = set_lds(k_scan_w<16, kLinear>, ldsw); if (rc) return rc;
+                     k_scan_w<16, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
+          default: { int rc = set_lds(k_scan_w<32, kLinear>, ldsw); if (rc) return rc;
+                     k_scan_w<32, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
+        }
       }
     } else if (mode == kLinear) {
       DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kLinear>, ldsw); if (rc) return rc;
