@@ -31,6 +31,22 @@ constexpr int kRowsPerLane = 4;        // rows scored per lane per tile
 constexpr int kWantBlocks = 256;       // blocks a small batch is split into (the chip has 256 CUs)
 constexpr int kMinTiles = 4;           // shortest chunk, in tiles
 constexpr int kPrepassBlocks = 256;    // blocks (tiles) of the bound-seeding pass, per query
+// Block-shared scalars of the streaming kernels.  They live at the END of the dynamic LDS
+// allocation: a kernel with no static __shared__ object gets its dynamic LDS at address 0, and
+// then the byte-permuted table address (see adc_row_rot) is the LDS address itself -- with static
+// objects in front the compiler has to add their size to every look-up address.
+struct BlockVars {
+  int total, off, last;
+  uint32_t tg;
+  int cnt;
+  uint32_t tau;
+  float red[16];
+  float scale[4];
+  int wave_cnt[16];
+};
+constexpr size_t kBlockVarsBytes = 256;
+static_assert(sizeof(BlockVars) <= kBlockVarsBytes, "BlockVars must fit its slot");
+
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kOrdMax = 0xFFFFFFFFu;
 
@@ -190,10 +206,34 @@ __device__ __forceinline__ float adc_row(const float* __restrict__ A, const uint
 // ascending-m sum the results are defined with, so it is used as a filter only: a row whose
 // rotated sum is not above (1 + kRotEps(M)) * bound has its ascending-m sum recomputed exactly.
 __host__ __device__ constexpr bool rot_m(int M) { return M == 8 || M == 16 || M == 32; }
+
+// The look-up table of the streaming kernels sits at LDS address 0 (they have no static
+// __shared__ object, and the host side verifies it: see require_table_at_lds_zero), so the
+// byte-permuted value IS the LDS address.  Reading through an address-space-3 pointer made from
+// that integer keeps the compiler from adding the (zero) address of the dynamic LDS symbol to
+// every look-up.
+typedef __attribute__((address_space(3))) const float lds_float;
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) const f32x2_t lds_float2;
+typedef __attribute__((address_space(3))) const u32x2_t lds_uint2;
+__device__ __forceinline__ float lds_read_f32(uint32_t addr) { return *reinterpret_cast<lds_float*>((uintptr_t)addr); }
+__device__ __forceinline__ float2 lds_read_f32x2(uint32_t addr) {
+  f32x2_t v = *reinterpret_cast<lds_float2*>((uintptr_t)addr);
+  return make_float2(v.x, v.y);
+}
+__device__ __forceinline__ uint2 lds_read_u32x2(uint32_t addr) {
+  u32x2_t v = *reinterpret_cast<lds_uint2*>((uintptr_t)addr);
+  return make_uint2(v.x, v.y);
+}
 // LDS bytes of one query's table: 256 x 64 slots in the rotated layout, [M][256] otherwise.
 __host__ __device__ constexpr size_t table_bytes(int M) { return rot_m(M) ? (size_t)65536 : (size_t)M * 1024; }
 // LDS of the bound-seeding kernel: the table plus, in the rotated layout, the staging copy used to fill it.
 __host__ __device__ constexpr size_t tau0_lds(int M) { return table_bytes(M) + (rot_m(M) ? (size_t)M * 1024 : 0); }
+// LDS of the single-block inverted-index kernel before its BlockVars: table + max(keys, staging copy).
+__host__ __device__ constexpr size_t ivf_lds_main(int M) {
+  return table_bytes(M) + ((size_t)2048 * 8 > (rot_m(M) ? (size_t)M * 1024 : 0) ? (size_t)2048 * 8 : (size_t)M * 1024);
+}
 
 // Both sums are within (M-1) u / (1 - (M-1) u) of the exact real sum of non-negative terms
 // (u = 2^-24), so they differ by less than a factor 1 + (M-1) 2^-23; M 2^-22 leaves room for
@@ -217,10 +257,9 @@ __device__ __forceinline__ void fill_table_rot(float* T, float* stage, const flo
   __syncthreads();
 }
 
-// Rotated-order sum for one stored row; lanebase = (row % 32) * 4.
+// The MT code bytes of one stored row as MT/4 words (16-byte loads for M >= 16).
 template <int MT>
-__device__ __forceinline__ float adc_row_rot(const float* T, const uint8_t* __restrict__ row, uint32_t lanebase) {
-  uint32_t w[MT / 4];
+__device__ __forceinline__ void load_row_words(const uint8_t* __restrict__ row, uint32_t (&w)[MT / 4]) {
   if constexpr (MT == 8) {
     uint2 v = *reinterpret_cast<const uint2*>(row);
     w[0] = v.x; w[1] = v.y;
@@ -232,14 +271,59 @@ __device__ __forceinline__ float adc_row_rot(const float* T, const uint8_t* __re
       w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
     }
   }
+}
+
+// One segment of a stored row: kRotSeg<MT> bytes (16, or 8 for M = 8), as words.
+template <int MT> constexpr int kRotSeg = MT >= 16 ? 16 : 8;
+template <int MT>
+__device__ __forceinline__ void load_row_segment(const uint8_t* __restrict__ row, int seg, uint32_t* w) {
+  if constexpr (MT == 8) {
+    uint2 v = *reinterpret_cast<const uint2*>(row);
+    w[0] = v.x; w[1] = v.y;
+  } else {
+    uint4 v = reinterpret_cast<const uint4*>(row)[seg];
+    w[4 * seg] = v.x; w[4 * seg + 1] = v.y; w[4 * seg + 2] = v.z; w[4 * seg + 3] = v.w;
+  }
+}
+
+// Rotated-order sum for one stored row given as words; lanebase = (row % 32) * 4.  kAtZero: T is
+// known to start at LDS address 0 (kernels without static LDS); otherwise T's address is added
+// per look-up.
+template <int MT, bool kAtZero = true>
+__device__ __forceinline__ float adc_words_rot(const float* T, const uint32_t (&w)[MT / 4], uint32_t lanebase) {
   float d = 0.f;
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     // byte 0 <- lanebase, byte 1 <- code byte t, bytes 2,3 <- 0
     uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lanebase, 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
-    d = __fadd_rn(d, *reinterpret_cast<const float*>(reinterpret_cast<const char*>(T) + addr + t * 4));
+    if constexpr (kAtZero) d = __fadd_rn(d, lds_read_f32(addr + t * 4));
+    else d = __fadd_rn(d, *reinterpret_cast<const float*>(reinterpret_cast<const char*>(T) + addr + t * 4));
   }
   return d;
+}
+
+// The two halves of adc_words_rot for the software-pipelined loops: first all LDS addresses of a
+// row (after which its code words are dead and the registers can take the next tile's row) ...
+template <int MT>
+__device__ __forceinline__ void rot_addrs(const uint32_t (&w)[MT / 4], uint32_t lanebase, uint32_t (&addr)[MT]) {
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+    addr[t] = __builtin_amdgcn_perm(w[t >> 2], lanebase, 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
+}
+// ... then the look-ups, table at LDS address 0
+template <int MT>
+__device__ __forceinline__ float rot_sum(const uint32_t (&addr)[MT]) {
+  float d = 0.f;
+#pragma unroll
+  for (int t = 0; t < MT; ++t) d = __fadd_rn(d, lds_read_f32(addr[t] + t * 4));
+  return d;
+}
+
+template <int MT, bool kAtZero = true>
+__device__ __forceinline__ float adc_row_rot(const float* T, const uint8_t* __restrict__ row, uint32_t lanebase) {
+  uint32_t w[MT / 4];
+  load_row_words<MT>(row, w);
+  return adc_words_rot<MT, kAtZero>(T, w, lanebase);
 }
 
 // Ascending-m sum for stored row number r (rotated storage), table in the T layout.
@@ -449,7 +533,7 @@ __global__ __launch_bounds__(kScanThreads) void k_tau0(ScanArgs a) {
   extern __shared__ __align__(16) uint8_t smem[];
   const int M = MT ? MT : a.M;
   float* A = reinterpret_cast<float*>(smem);
-  __shared__ int s_last;
+  BlockVars* bv = reinterpret_cast<BlockVars*>(smem + tau0_lds(M));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
   const int64_t q = blockIdx.y;
@@ -500,9 +584,9 @@ __global__ __launch_bounds__(kScanThreads) void k_tau0(ScanArgs a) {
   if (lane == 0) __hip_atomic_store(minima + blockIdx.x * nwaves + wave, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   wait_own_memory_ops();
   __syncthreads();
-  if (tid == 0) s_last = atomicAdd(a.counter + q, 1u) == gridDim.x - 1;
+  if (tid == 0) bv->last = atomicAdd(a.counter + q, 1u) == gridDim.x - 1;
   __syncthreads();
-  if (!s_last || wave != 0) return;
+  if (!bv->last || wave != 0) return;
   // k-th smallest of the G minima, most significant bit first: bit b of the answer is 0 when at
   // least k values lie below (answer | 1 << b).  Each lane keeps its share of the values in registers.
   const int k = a.k;
@@ -694,11 +778,13 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
   const int M = MT ? MT : a.M;
   float* A = reinterpret_cast<float*>(smem);
   uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + table_bytes(M));  // [waves + 1][kWaveCap]
-  __shared__ int s_total, s_off, s_last;
-  __shared__ uint32_t s_tg;
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
+  BlockVars* bv = reinterpret_cast<BlockVars*>(wbuf + (size_t)(nwaves + 1) * kWaveCap);
+  int& s_total = bv->total;
+  int& s_off = bv->off;
+  int& s_last = bv->last;
+  uint32_t& s_tg = bv->tg;
   const int64_t q = blockIdx.y;
   uint64_t* cand = a.partial + q * a.cand_cap;
   if (a.qmode && a.qmode[q] != a.want_mode) return;
@@ -733,6 +819,26 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
     // still a valid bound); thousands of waves polling one address would serialise on it.
     uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    // Software pipeline over the tiles (rotated form): the code words of tile t+1 are requested
+    // while tile t is scored.  Per row, all LDS addresses are formed first; the row's words are
+    // dead from then on and their registers receive the next tile's row before the look-ups
+    // start.  Row numbers past the chunk's end are clamped to its last row (valid memory) and
+    // masked when they are scored; the ids of a target list run one more tile ahead.
+    auto id_at = [&](int64_t tile, int r) -> int32_t {
+      int64_t i = tile + (int64_t)r * blockDim.x + tid;
+      if (i >= r1) i = r1 - 1;
+      return MODE == kLinear ? (int32_t)i : tids[i];
+    };
+    [[maybe_unused]] int32_t rid[kRowsPerLane], rid_n[kRowsPerLane];
+    [[maybe_unused]] uint32_t w[kRowsPerLane][rot_m(MT) ? MT / 4 : 1];
+    if constexpr (rot_m(MT)) {
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) rid[r] = id_at(r0, r);
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + (int64_t)rid[r] * M, w[r]);
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) rid_n[r] = id_at(r0 + tile_step, r);
+    }
     for (int64_t tile = r0; tile < r1; tile += tile_step) {
       uint64_t key[kRowsPerLane];
       uint32_t pend = 0;
@@ -742,19 +848,22 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
       if constexpr (rot_m(MT)) {
         // filter on the conflict-free rotated-order sum; exact ascending-m sum for the few rows that pass
         const float fb = rot_filter(bound, rot_eps(MT));
-        int32_t rid[kRowsPerLane];
-        uint32_t maybe = 0;
+        int32_t rid_nn[kRowsPerLane];
+        uint32_t live = 0, maybe = 0;
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
-          int64_t i = tile + (int64_t)r * blockDim.x + tid;
           key[r] = kKeyMax;
-          rid[r] = 0;
-          if (i < r1) {
-            rid[r] = MODE == kLinear ? (int32_t)i : tids[i];
-            float df = adc_row_rot<MT>(A, a.codes + (int64_t)rid[r] * M, ((uint32_t)rid[r] & 31u) << 2);
-            if (df <= fb) maybe |= 1u << r;
-          }
+          if (tile + (int64_t)r * blockDim.x + tid < r1) live |= 1u << r;
+          rid_nn[r] = id_at(tile + 2 * tile_step, r);
         }
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          uint32_t addr[MT];
+          rot_addrs<MT>(w[r], ((uint32_t)rid[r] & 31u) << 2, addr);
+          load_row_words<MT>(a.codes + (int64_t)rid_n[r] * M, w[r]);
+          if (rot_sum<MT>(addr) <= fb) maybe |= 1u << r;
+        }
+        maybe &= live;
         if (__ballot(maybe != 0) != 0ull) {
 #pragma unroll
           for (int r = 0; r < kRowsPerLane; ++r) {
@@ -764,6 +873,11 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
               if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
             }
           }
+        }
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          rid[r] = rid_n[r];
+          rid_n[r] = rid_nn[r];
         }
       } else {
 #pragma unroll
@@ -829,7 +943,9 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
   uint64_t* wbuf1 = wbuf0 + (size_t)(nwaves + 1) * kWaveCap;          // query 1
-  __shared__ int s_total, s_off;
+  BlockVars* bv = reinterpret_cast<BlockVars*>(wbuf1 + (size_t)(nwaves + 1) * kWaveCap);
+  int& s_total = bv->total;
+  int& s_off = bv->off;
   const int64_t q0 = 2 * (int64_t)blockIdx.y, q1 = q0 + 1;
   const int k = a.k;
   const int64_t nrows = a.N;
@@ -853,47 +969,63 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
     }
     __syncthreads();
   }
-  uint32_t lb[MT];  // slot offset of step t for this lane: rows are dealt so that row % 32 == tid % 32
+  // Slot offset of step t for this lane, ((tid + t) % 32) * 8 (rows are dealt so that row % 32 ==
+  // tid % 32): one byte each, four steps to a register; the byte permute that builds an LDS
+  // address takes its low byte from here and its second byte from the code word.
+  uint32_t lb4[MT / 4];
 #pragma unroll
-  for (int t = 0; t < MT; ++t) lb[t] = (uint32_t)((tid + t) & 31) * 8u;
+  for (int j = 0; j < MT / 4; ++j) {
+    lb4[j] = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) lb4[j] |= ((uint32_t)((tid + 4 * j + b) & 31) * 8u) << (8 * b);
+  }
 
   uint64_t* buf0 = wbuf0 + (size_t)wave * kWaveCap;
   uint64_t* buf1 = wbuf1 + (size_t)wave * kWaveCap;
   int cnt0 = 0, cnt1 = 0;
   uint32_t tau0 = kOrdMax, tau1 = kOrdMax;
   const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
+  // row of slot r in the tile at `tile`; past the end: the last row (valid memory, masked later)
+  auto row_at = [&](int64_t tile, int r) -> int64_t {
+    int64_t i = tile + (int64_t)r * blockDim.x + tid;
+    return i < nrows ? i : nrows - 1;
+  };
+  uint32_t w[kRowsPerLane][MT / 4];
+#pragma unroll
+  for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(0, r) * MT, w[r]);
   for (int64_t tile = 0; tile < nrows; tile += tile_step) {
     const float fb0 = rot_filter(tau0, rot_eps(MT)), fb1 = rot_filter(tau1, rot_eps(MT));
     uint32_t maybe0 = 0, maybe1 = 0;
+    // software pipeline as in k_scan_w, in segments of 16 code bytes: a segment's LDS addresses
+    // first, then the request for the same segment of the next tile's row into the registers
+    // just freed, then the look-ups
+    uint32_t live = 0;
 #pragma unroll
     for (int r = 0; r < kRowsPerLane; ++r) {
-      const int64_t i = tile + (int64_t)r * blockDim.x + tid;
-      if (i < nrows) {
-        const uint8_t* row = a.codes + i * MT;
-        uint32_t w[MT / 4];
-        if constexpr (MT == 8) {
-          uint2 v = *reinterpret_cast<const uint2*>(row);
-          w[0] = v.x; w[1] = v.y;
-        } else {
-          const uint4* p = reinterpret_cast<const uint4*>(row);
+      if (tile + (int64_t)r * blockDim.x + tid < nrows) live |= 1u << r;
+      const uint8_t* next_row = a.codes + row_at(tile + tile_step, r) * MT;
+      float d0 = 0.f, d1 = 0.f;
 #pragma unroll
-          for (int j = 0; j < MT / 16; ++j) {
-            uint4 v = p[j];
-            w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
-          }
+      for (int sg = 0; sg < MT / kRotSeg<MT>; ++sg) {
+        uint32_t addr[kRotSeg<MT>];
+#pragma unroll
+        for (int u = 0; u < kRotSeg<MT>; ++u) {
+          const int t = sg * kRotSeg<MT> + u;
+          addr[u] = __builtin_amdgcn_perm(w[r][t >> 2], lb4[t >> 2], 0x0c0c0400u | ((uint32_t)(t & 3) * 0x0101u));
         }
-        float d0 = 0.f, d1 = 0.f;
+        load_row_segment<MT>(next_row, sg, w[r]);
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-          uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lb[t], 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
-          float2 v = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(T2) + addr);
+        for (int u = 0; u < kRotSeg<MT>; ++u) {
+          float2 v = lds_read_f32x2(addr[u]);  // T2 is at LDS address 0
           d0 = __fadd_rn(d0, v.x);
           d1 = __fadd_rn(d1, v.y);
         }
-        if (d0 <= fb0) maybe0 |= 1u << r;
-        if (d1 <= fb1) maybe1 |= 1u << r;
       }
+      if (d0 <= fb0) maybe0 |= 1u << r;
+      if (d1 <= fb1) maybe1 |= 1u << r;
     }
+    maybe0 &= live;
+    maybe1 &= live;
     if (__ballot((maybe0 | maybe1) != 0) != 0ull) {
       uint64_t key[kRowsPerLane];
       uint32_t pend = 0;
@@ -942,6 +1074,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
 // buffer of kWaveCap4 keys per query.
 constexpr int kWaveCap4 = 128;
 constexpr int kWaveK4 = 100;  // largest topk this kernel takes (must stay below kWaveCap4)
+constexpr int kRescoreCap = 128;  // per-wave queue of rows awaiting their exact score
 
 // ascending-m fp32 sum for stored row r (rotated form), table A = lut[M][256] in global memory
 template <int MT>
@@ -957,14 +1090,17 @@ template <int MT>
 __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
   static_assert(rot_m(MT), "rotated stored form only");
   extern __shared__ __align__(16) uint8_t smem[];
-  uint2* T4 = reinterpret_cast<uint2*>(smem);                          // [256][32] x 4 halves
+  // smem[0 .. 65536): T4 [256][32] x 4 halves, at LDS address 0
   uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + 65536);          // [4][waves + 1][kWaveCap4]
-  __shared__ float s_red[kScanThreads / 64];
-  __shared__ float s_scale[4];
-  __shared__ int s_total, s_off;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
   const size_t qstride = (size_t)(nwaves + 1) * kWaveCap4;
+  uint64_t* rq = wbuf + 4 * qstride + (size_t)wave * kRescoreCap;      // [waves][kRescoreCap] (query, row)
+  BlockVars* bv = reinterpret_cast<BlockVars*>(wbuf + 4 * qstride + (size_t)nwaves * kRescoreCap);
+  float* s_red = bv->red;
+  float* s_scale = bv->scale;
+  int& s_total = bv->total;
+  int& s_off = bv->off;
   const int64_t q0 = 4 * (int64_t)blockIdx.y;
   const int k = a.k;
   const int64_t nrows = a.N;
@@ -1009,16 +1145,51 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
       __syncthreads();
     }
   }
-  uint32_t lb[MT];  // slot offset of step t for this lane: rows are dealt so that row % 32 == tid % 32
+  // Slot offset of step t for this lane, ((tid + t) % 32) * 8 (rows are dealt so that row % 32 ==
+  // tid % 32): one byte each, four steps to a register; the byte permute that builds an LDS
+  // address takes its low byte from here and its second byte from the code word.
+  uint32_t lb4[MT / 4];
 #pragma unroll
-  for (int t = 0; t < MT; ++t) lb[t] = (uint32_t)((tid + t) & 31) * 8u;
+  for (int j = 0; j < MT / 4; ++j) {
+    lb4[j] = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) lb4[j] |= ((uint32_t)((tid + 4 * j + b) & 31) * 8u) << (8 * b);
+  }
   const float scale0 = s_scale[0], scale1 = s_scale[1], scale2 = s_scale[2], scale3 = s_scale[3];
   const float rel = 1.f + 1.1f * (float)MT * 4.8828125e-4f;   // 1 + 1.1 M 2^-11
   const float slack = (float)MT * 1.1920929e-7f;               // M 2^-23
 
   int cnt[4] = {0, 0, 0, 0};
   uint32_t tau[4] = {kOrdMax, kOrdMax, kOrdMax, kOrdMax};
+  int qn = 0;  // entries in this wave's re-score queue (wave-uniform)
+  // Exact ascending-m scores for queue entries [first, first + n), n <= 64, one per lane, from
+  // the fp32 tables in global memory; each goes to its query's candidate buffer.
+  auto rescore = [&](int first, int n) {
+    wave_sync();  // the queue was written by other lanes
+    uint64_t key[1] = {kKeyMax};
+    int jq = -1;
+    if (lane < n) {
+      const uint64_t e = rq[first + lane];
+      jq = (int)(e >> 32);
+      const int64_t i = (int64_t)(uint32_t)e;
+      key[0] = make_key(adc_row_unrot_global<MT>(a.lut + (q0 + jq) * MT * 256, a.codes + i * MT, i), (int32_t)i);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t pend = (jq == j && (uint32_t)(key[0] >> 32) <= tau[j]) ? 1u : 0u;
+      if (__ballot(pend != 0) != 0ull)
+        wave_offer<1>(wbuf + j * qstride + (size_t)wave * kWaveCap4, cnt[j], tau[j], k, key, pend, lane, kWaveCap4);
+    }
+  };
   const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
+  // row of slot r in the tile at `tile`; past the end: the last row (valid memory, masked later)
+  auto row_at = [&](int64_t tile, int r) -> int64_t {
+    int64_t i = tile + (int64_t)r * blockDim.x + tid;
+    return i < nrows ? i : nrows - 1;
+  };
+  uint32_t w[kRowsPerLane][MT / 4];
+#pragma unroll
+  for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(0, r) * MT, w[r]);
   for (int64_t tile = 0; tile < nrows; tile += tile_step) {
     float fb[4];
     const float scl[4] = {scale0, scale1, scale2, scale3};
@@ -1026,59 +1197,64 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
     for (int j = 0; j < 4; ++j)
       fb[j] = tau[j] == kOrdMax ? __uint_as_float(0x7F800000u) : float_of_ord(tau[j]) * scl[j] * rel + slack;
     uint32_t maybe[4] = {0, 0, 0, 0};
+    // software pipeline as in k_scan_w, in segments of 16 code bytes: a segment's LDS addresses
+    // first, then the request for the same segment of the next tile's row into the registers
+    // just freed, then the look-ups
+    uint32_t live = 0;
 #pragma unroll
     for (int r = 0; r < kRowsPerLane; ++r) {
-      const int64_t i = tile + (int64_t)r * blockDim.x + tid;
-      if (i < nrows) {
-        const uint8_t* row = a.codes + i * MT;
-        uint32_t w[MT / 4];
-        if constexpr (MT == 8) {
-          uint2 v = *reinterpret_cast<const uint2*>(row);
-          w[0] = v.x; w[1] = v.y;
-        } else {
-          const uint4* p = reinterpret_cast<const uint4*>(row);
+      if (tile + (int64_t)r * blockDim.x + tid < nrows) live |= 1u << r;
+      const uint8_t* next_row = a.codes + row_at(tile + tile_step, r) * MT;
+      __half2 acc01 = __float2half2_rn(0.f), acc23 = __float2half2_rn(0.f);
 #pragma unroll
-          for (int jj = 0; jj < MT / 16; ++jj) {
-            uint4 v = p[jj];
-            w[4 * jj] = v.x; w[4 * jj + 1] = v.y; w[4 * jj + 2] = v.z; w[4 * jj + 3] = v.w;
-          }
+      for (int sg = 0; sg < MT / kRotSeg<MT>; ++sg) {
+        uint32_t addr[kRotSeg<MT>];
+#pragma unroll
+        for (int u = 0; u < kRotSeg<MT>; ++u) {
+          const int t = sg * kRotSeg<MT> + u;
+          addr[u] = __builtin_amdgcn_perm(w[r][t >> 2], lb4[t >> 2], 0x0c0c0400u | ((uint32_t)(t & 3) * 0x0101u));
         }
-        __half2 acc01 = __float2half2_rn(0.f), acc23 = __float2half2_rn(0.f);
+        load_row_segment<MT>(next_row, sg, w[r]);
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-          uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lb[t], 0x0c0c0400u | ((uint32_t)(t & 3) << 8));
-          uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(T4) + addr);
+        for (int u = 0; u < kRotSeg<MT>; ++u) {
+          uint2 v = lds_read_u32x2(addr[u]);  // T4 is at LDS address 0
           acc01 = __hadd2(acc01, *reinterpret_cast<const __half2*>(&v.x));
           acc23 = __hadd2(acc23, *reinterpret_cast<const __half2*>(&v.y));
         }
-        if (__low2float(acc01) <= fb[0]) maybe[0] |= 1u << r;
-        if (__high2float(acc01) <= fb[1]) maybe[1] |= 1u << r;
-        if (__low2float(acc23) <= fb[2]) maybe[2] |= 1u << r;
-        if (__high2float(acc23) <= fb[3]) maybe[3] |= 1u << r;
       }
+      if (__low2float(acc01) <= fb[0]) maybe[0] |= 1u << r;
+      if (__high2float(acc01) <= fb[1]) maybe[1] |= 1u << r;
+      if (__low2float(acc23) <= fb[2]) maybe[2] |= 1u << r;
+      if (__high2float(acc23) <= fb[3]) maybe[3] |= 1u << r;
     }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) maybe[j] &= live;
+    // Rows that pass a filter are not re-scored on the spot (one or two lanes busy, the wave
+    // waiting on their table reads from global memory) but queued as (query, row); a full
+    // wavefront of 64 queued entries is then re-scored at once, one entry per lane.
     if (__ballot((maybe[0] | maybe[1] | maybe[2] | maybe[3]) != 0) != 0ull) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (__ballot(maybe[j] != 0) == 0ull) continue;  // wave-uniform
-        const float* A = a.lut + (q0 + j) * MT * 256;
-        uint64_t key[kRowsPerLane];
-        uint32_t pend = 0;
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
-          key[r] = kKeyMax;
-          if (maybe[j] & (1u << r)) {
+          const bool hit = (maybe[j] >> r) & 1u;
+          const unsigned long long m = __ballot(hit);
+          if (m == 0ull) continue;
+          if (hit) {
             const int64_t i = tile + (int64_t)r * blockDim.x + tid;
-            key[r] = make_key(adc_row_unrot_global<MT>(A, a.codes + i * MT, i), (int32_t)i);
-            if ((uint32_t)(key[r] >> 32) <= tau[j]) pend |= 1u << r;
+            rq[qn + __popcll(m & ((1ull << lane) - 1ull))] = ((uint64_t)j << 32) | (uint32_t)i;
+          }
+          qn += __popcll(m);
+          if (qn >= 64) {  // at most 127 entries are ever queued: kRescoreCap holds them
+            qn -= 64;
+            rescore(qn, 64);
           }
         }
-        if (__ballot(pend != 0) != 0ull)
-          wave_offer<kRowsPerLane>(wbuf + j * qstride + (size_t)wave * kWaveCap4, cnt[j], tau[j], k, key, pend, lane,
-                                   kWaveCap4);
       }
     }
   }
+  if (qn > 0) rescore(0, qn);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     uint64_t* best;
@@ -1248,9 +1424,10 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
   const int M = MT ? MT : a.M;
   float* A = reinterpret_cast<float*>(smem);
   uint64_t* keys = reinterpret_cast<uint64_t*>(smem + table_bytes(M));
-  __shared__ int s_cnt;
-  __shared__ uint32_t s_tau;
-  __shared__ int s_wave[kScanThreads / 64];
+  BlockVars* bv = reinterpret_cast<BlockVars*>(smem + ivf_lds_main(M));
+  int& s_cnt = bv->cnt;
+  uint32_t& s_tau = bv->tau;
+  int* s_wave = bv->wave_cnt;
 
   const int tid = threadIdx.x;
   const int64_t q = blockIdx.x;
@@ -1295,7 +1472,8 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
         bool maybe = true;
         if constexpr (rot_m(MT)) {
           // the list-ordered copy is rotated by position; filter on the rotated-order sum first
-          d = adc_row_rot<MT>(A, a.codes_list + pos * M, ((uint32_t)pos & 31u) << 2);
+          // (the block-wide vote in sel_offer brings static LDS with it: the table is not at 0)
+          d = adc_row_rot<MT, false>(A, a.codes_list + pos * M, ((uint32_t)pos & 31u) << 2);
           maybe = d <= rot_filter(s_tau, rot_eps(MT));
           if (maybe) d = adc_row_exact_rot<MT>(A, a.codes_list + pos * M, pos);
         } else {
@@ -1324,9 +1502,12 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
   const int M = MT ? MT : a.M;
   float* A = reinterpret_cast<float*>(smem);
   uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + table_bytes(M));  // [waves + 1][kWaveCap]
-  __shared__ int s_total, s_off, s_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
+  BlockVars* bv = reinterpret_cast<BlockVars*>(wbuf + (size_t)(nwaves + 1) * kWaveCap);
+  int& s_total = bv->total;
+  int& s_off = bv->off;
+  int& s_last = bv->last;
   const int64_t q = blockIdx.y;
   uint64_t* cand = a.cand + q * a.cand_cap;
   const int k = a.k;
@@ -1700,6 +1881,29 @@ int set_lds(Kern kern, size_t bytes) {
   return RII_OK;
 }
 
+// set_lds for the kernels whose table must sit at LDS address 0 (checked once per kernel)
+template <typename Kern>
+int set_lds0(Kern kern, size_t bytes) {
+  static int checked = -1;  // one instance per kernel type and address
+  static const void* which = nullptr;
+  if (checked < 0 || which != reinterpret_cast<const void*>(kern)) {
+    int rc = require_table_at_lds_zero(kern);
+    if (rc) return rc;
+    checked = 1;
+    which = reinterpret_cast<const void*>(kern);
+  }
+  return set_lds(kern, bytes);
+}
+
+// The kernels that address their table as "LDS address 0" must not have static LDS in front of
+// the dynamic allocation; refuse to launch otherwise.
+template <typename Kern>
+int require_table_at_lds_zero(Kern kern) {
+  hipFuncAttributes attr{};
+  RII_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
+  return attr.sharedSizeBytes == 0 ? RII_OK : RII_ERR_DEVICE;
+}
+
 #define DISPATCH_M(M, ...)                                  \
   switch (M) {                                              \
     case 8: { constexpr int MT = 8; __VA_ARGS__; } break;   \
@@ -1766,7 +1970,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     pre.minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * nchunks * topk);
     pre.counter = pre_counter;
     dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
-    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
     if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2) {
       // Large batch, every block owns its queries' whole scan: four queries per block with the
       // half-precision filter (k_scan_w4) when topk allows, then two per block (k_scan_w2) and a
@@ -1781,17 +1985,18 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
         b.dist = dist ? dist + (size_t)o * out_stride : nullptr;
         return b;
       };
-      const size_t lds4 = 65536 + 4 * (size_t)(kScanThreads / 64 + 1) * kWaveCap4 * 8;
-      const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+      const size_t lds4 = 65536 + 4 * (size_t)(kScanThreads / 64 + 1) * kWaveCap4 * 8 +
+                          (size_t)(kScanThreads / 64) * kRescoreCap * 8 + kBlockVarsBytes;
+      const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
       int done = 0;
       if (topk <= kWaveK4 && Q >= 4) {
         dim3 g4(1, (unsigned)(Q / 4));
         switch (M) {
-          case 8: { int rc = set_lds(k_scan_w4<8>, lds4); if (rc) return rc;
+          case 8: { int rc = set_lds0(k_scan_w4<8>, lds4); if (rc) return rc;
                     k_scan_w4<8><<<g4, kScanThreads, lds4, st>>>(a); } break;
-          case 16: { int rc = set_lds(k_scan_w4<16>, lds4); if (rc) return rc;
+          case 16: { int rc = set_lds0(k_scan_w4<16>, lds4); if (rc) return rc;
                      k_scan_w4<16><<<g4, kScanThreads, lds4, st>>>(a); } break;
-          default: { int rc = set_lds(k_scan_w4<32>, lds4); if (rc) return rc;
+          default: { int rc = set_lds0(k_scan_w4<32>, lds4); if (rc) return rc;
                      k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a); } break;
         }
         done = Q / 4 * 4;
@@ -1800,11 +2005,11 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
         ScanArgs b = shifted(done);
         dim3 g2(1, (unsigned)((Q - done) / 2));
         switch (M) {
-          case 8: { int rc = set_lds(k_scan_w2<8>, lds2); if (rc) return rc;
+          case 8: { int rc = set_lds0(k_scan_w2<8>, lds2); if (rc) return rc;
                     k_scan_w2<8><<<g2, kScanThreads, lds2, st>>>(b); } break;
-          case 16: { int rc = set_lds(k_scan_w2<16>, lds2); if (rc) return rc;
+          case 16: { int rc = set_lds0(k_scan_w2<16>, lds2); if (rc) return rc;
                      k_scan_w2<16><<<g2, kScanThreads, lds2, st>>>(b); } break;
-          default: { int rc = set_lds(k_scan_w2<32>, lds2); if (rc) return rc;
+          default: { int rc = set_lds0(k_scan_w2<32>, lds2); if (rc) return rc;
                      k_scan_w2<32><<<g2, kScanThreads, lds2, st>>>(b); } break;
         }
         done += (Q - done) / 2 * 2;
@@ -1812,23 +2017,23 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
       if (Q - done == 1) {
         ScanArgs b = shifted(done);
         switch (M) {
-          case 8: { int rc = set_lds(k_scan_w<8, kLinear>, ldsw); if (rc) return rc;
+          case 8: { int rc = set_lds0(k_scan_w<8, kLinear>, ldsw); if (rc) return rc;
                     k_scan_w<8, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
-          case 16: { int rc = set_lds(k_scan_w<16, kLinear>, ldsw); if (rc) return rc;
+          case 16: { int rc = set_lds0(k_scan_w<16, kLinear>, ldsw); if (rc) return rc;
                      k_scan_w<16, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
-          default: { int rc = set_lds(k_scan_w<32, kLinear>, ldsw); if (rc) return rc;
+          default: { int rc = set_lds0(k_scan_w<32, kLinear>, ldsw); if (rc) return rc;
                      k_scan_w<32, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
         }
       }
     } else if (mode == kLinear) {
-      DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kLinear>, ldsw); if (rc) return rc;
-                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kLinear>, tau0_lds(M)); if (rc2) return rc2; }
-                      if (prepass) k_tau0<MT, kLinear><<<pgrid, kScanThreads, tau0_lds(M), st>>>(pre);
+      DISPATCH_M(M, { int rc = set_lds0(k_scan_w<MT, kLinear>, ldsw); if (rc) return rc;
+                      if (prepass) { int rc2 = set_lds0(k_tau0<MT, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc2) return rc2; }
+                      if (prepass) k_tau0<MT, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre);
                       k_scan_w<MT, kLinear><<<grid, kScanThreads, ldsw, st>>>(a); });
     } else {
-      DISPATCH_M(M, { int rc = set_lds(k_scan_w<MT, kSubset>, ldsw); if (rc) return rc;
-                      if (prepass) { int rc2 = set_lds(k_tau0<MT, kSubset>, tau0_lds(M)); if (rc2) return rc2; }
-                      if (prepass) k_tau0<MT, kSubset><<<pgrid, kScanThreads, tau0_lds(M), st>>>(pre);
+      DISPATCH_M(M, { int rc = set_lds0(k_scan_w<MT, kSubset>, ldsw); if (rc) return rc;
+                      if (prepass) { int rc2 = set_lds0(k_tau0<MT, kSubset>, tau0_lds(M) + kBlockVarsBytes); if (rc2) return rc2; }
+                      if (prepass) k_tau0<MT, kSubset><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre);
                       k_scan_w<MT, kSubset><<<grid, kScanThreads, ldsw, st>>>(a); });
     }
   } else {
@@ -1994,14 +2199,14 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
     a.cand = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(ws) + 4 * cstride * 4);
     a.cand_cap = (int64_t)split * topk;
     k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
-    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8;
+    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
     dim3 grid((unsigned)split, (unsigned)Q);
-    DISPATCH_M(M, { int rc = set_lds(k_ivf_w<MT>, ldsw); if (rc) return rc;
+    DISPATCH_M(M, { int rc = set_lds0(k_ivf_w<MT>, ldsw); if (rc) return rc;
                     k_ivf_w<MT><<<grid, kScanThreads, ldsw, st>>>(a); });
     RII_HIP(hipGetLastError());
     return RII_OK;
   }
-  const size_t lds = table_bytes(M) + std::max<size_t>((size_t)kSelCap * 8, rot_m(M) ? (size_t)M * 1024 : 0);
+  const size_t lds = ivf_lds_main(M) + kBlockVarsBytes;
   DISPATCH_M(M, { int rc = set_lds(k_ivf<MT>, lds); if (rc) return rc;
                   k_ivf<MT><<<Q, kScanThreads, lds, st>>>(a); });
   RII_HIP(hipGetLastError());
