@@ -373,6 +373,7 @@ struct ScanArgs {
   int out_stride;
   uint32_t* minima;              // bound-seeding pass: [Q][gridDim.x * waves] smallest distance image per wave
   uint32_t* counter;             // bound-seeding pass: [Q] blocks finished
+  int nq;                        // k_scan_w4: queries in the batch (the last group may be short)
 };
 
 enum { kLinear = 0, kSubset = 1 };
@@ -1072,9 +1073,14 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
 // Rows that pass are re-scored from the fp32 table in global memory, in ascending sub-space
 // order; results are therefore exactly those of the fp32 kernels.  Each wave keeps one candidate
 // buffer of kWaveCap4 keys per query.
+// When the batch alone does not give the chip several rounds of blocks, the code array is cut
+// into row chunks (grid.y, see plan_batch) and the chunks' results meet in the per-query
+// candidate lists as in k_scan_w; k_tau0 seeds the bounds first.
 constexpr int kWaveCap4 = 128;
 constexpr int kWaveK4 = 100;  // largest topk this kernel takes (must stay below kWaveCap4)
 constexpr int kRescoreCap = 128;  // per-wave queue of rows awaiting their exact score
+constexpr int kBatchWantBlocks = 1024;  // blocks wanted from a batched launch (four rounds of the chip)
+constexpr int kBatchMinTiles = 64;      // never cut the rows into chunks shorter than this many tiles
 
 // ascending-m fp32 sum for stored row r (rotated form), table A = lut[M][256] in global memory
 template <int MT>
@@ -1101,9 +1107,16 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
   float* s_scale = bv->scale;
   int& s_total = bv->total;
   int& s_off = bv->off;
-  const int64_t q0 = 4 * (int64_t)blockIdx.y;
+  // grid = (query groups, row chunks), query group fastest: the blocks resident at one time
+  // work on the same chunk of the code array, which the memory-side cache can then serve
+  const int64_t q0 = 4 * (int64_t)blockIdx.x;
+  // a short last group scores its last query again in the unused places and drops the copies
+  const int nlive = a.nq - q0 < 4 ? (int)(a.nq - q0) : 4;
+  auto qsrc = [&](int j) -> int64_t { return q0 + (j < nlive ? j : nlive - 1); };
   const int k = a.k;
-  const int64_t nrows = a.N;
+  const int64_t r0 = (int64_t)blockIdx.y * a.chunk_rows;
+  const int64_t nrows = r0 + a.chunk_rows < a.N ? r0 + a.chunk_rows : a.N;  // end of this block's rows
+  const bool chunked = gridDim.y > 1;
 
   // tables: one query at a time through a staging copy (the buffer area), scaled, rounded to
   // fp16 and written along diagonals (see fill_table_rot)
@@ -1111,7 +1124,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
     float* stage = reinterpret_cast<float*>(wbuf);
     __half* T4h = reinterpret_cast<__half*>(smem);
     for (int j = 0; j < 4; ++j) {
-      const float* lut = a.lut + (q0 + j) * MT * 256;
+      const float* lut = a.lut + qsrc(j) * MT * 256;
       float mx = 0.f;
       for (int i = tid; i < MT * 256; i += blockDim.x) {
         float v = lut[i];
@@ -1161,6 +1174,13 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
 
   int cnt[4] = {0, 0, 0, 0};
   uint32_t tau[4] = {kOrdMax, kOrdMax, kOrdMax, kOrdMax};
+  // With several chunks per query, the blocks of earlier chunks have left the query's bound in
+  // tau_g; it is read once here (the waves' own bounds take over from there).
+  uint32_t tg[4] = {kOrdMax, kOrdMax, kOrdMax, kOrdMax};
+  if (chunked) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tg[j] = __hip_atomic_load(a.tau_g + qsrc(j), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   int qn = 0;  // entries in this wave's re-score queue (wave-uniform)
   // Exact ascending-m scores for queue entries [first, first + n), n <= 64, one per lane, from
   // the fp32 tables in global memory; each goes to its query's candidate buffer.
@@ -1172,11 +1192,12 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
       const uint64_t e = rq[first + lane];
       jq = (int)(e >> 32);
       const int64_t i = (int64_t)(uint32_t)e;
-      key[0] = make_key(adc_row_unrot_global<MT>(a.lut + (q0 + jq) * MT * 256, a.codes + i * MT, i), (int32_t)i);
+      key[0] = make_key(adc_row_unrot_global<MT>(a.lut + qsrc(jq) * MT * 256, a.codes + i * MT, i), (int32_t)i);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t pend = (jq == j && (uint32_t)(key[0] >> 32) <= tau[j]) ? 1u : 0u;
+      const uint32_t bound = tau[j] < tg[j] ? tau[j] : tg[j];
+      const uint32_t pend = (jq == j && (uint32_t)(key[0] >> 32) <= bound) ? 1u : 0u;
       if (__ballot(pend != 0) != 0ull)
         wave_offer<1>(wbuf + j * qstride + (size_t)wave * kWaveCap4, cnt[j], tau[j], k, key, pend, lane, kWaveCap4);
     }
@@ -1189,13 +1210,15 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
   };
   uint32_t w[kRowsPerLane][MT / 4];
 #pragma unroll
-  for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(0, r) * MT, w[r]);
-  for (int64_t tile = 0; tile < nrows; tile += tile_step) {
+  for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(r0, r) * MT, w[r]);
+  for (int64_t tile = r0; tile < nrows; tile += tile_step) {
     float fb[4];
     const float scl[4] = {scale0, scale1, scale2, scale3};
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      fb[j] = tau[j] == kOrdMax ? __uint_as_float(0x7F800000u) : float_of_ord(tau[j]) * scl[j] * rel + slack;
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t bound = tau[j] < tg[j] ? tau[j] : tg[j];
+      fb[j] = bound == kOrdMax ? __uint_as_float(0x7F800000u) : float_of_ord(bound) * scl[j] * rel + slack;
+    }
     uint32_t maybe[4] = {0, 0, 0, 0};
     // software pipeline as in k_scan_w, in segments of 16 code bytes: a segment's LDS addresses
     // first, then the request for the same segment of the next tile's row into the registers
@@ -1228,7 +1251,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
       if (__high2float(acc23) <= fb[3]) maybe[3] |= 1u << r;
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) maybe[j] &= live;
+    for (int j = 0; j < 4; ++j) maybe[j] = j < nlive ? maybe[j] & live : 0u;
     // Rows that pass a filter are not re-scored on the spot (one or two lanes busy, the wave
     // waiting on their table reads from global memory) but queued as (query, row); a full
     // wavefront of 64 queued entries is then re-scored at once, one entry per lane.
@@ -1255,11 +1278,34 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
     }
   }
   if (qn > 0) rescore(0, qn);
+  if (!chunked) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j >= nlive) break;  // block-uniform
+      uint64_t* best;
+      int c = block_collect(wbuf + j * qstride, nwaves, cnt[j], tau[j], tau[j], k, &best, &s_total, &s_off, kWaveCap4);
+      write_result(best, c, k, a.ids + (q0 + j) * a.out_stride, a.dist ? a.dist + (q0 + j) * a.out_stride : nullptr);
+      __syncthreads();
+    }
+    return;
+  }
+  // Several chunks per query: the block's best keys go to each query's candidate list (all four
+  // first: the final selection re-uses the whole buffer area), then the block that arrives last
+  // for a query selects its result.
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
+    if (j >= nlive) break;  // block-uniform
+    const uint32_t bound = tau[j] < tg[j] ? tau[j] : tg[j];
     uint64_t* best;
-    int c = block_collect(wbuf + j * qstride, nwaves, cnt[j], tau[j], tau[j], k, &best, &s_total, &s_off, kWaveCap4);
-    write_result(best, c, k, a.ids + (q0 + j) * a.out_stride, a.dist ? a.dist + (q0 + j) * a.out_stride : nullptr);
+    int c = block_collect(wbuf + j * qstride, nwaves, cnt[j], tau[j], bound, k, &best, &s_total, &s_off, kWaveCap4);
+    publish_block_result(best, c, k, a.partial + (q0 + j) * a.cand_cap, a.cand_cnt + q0 + j, a.tau_g + q0 + j, &s_off);
+    __syncthreads();
+  }
+#pragma unroll 1
+  for (int j = 0; j < nlive; ++j) {
+    finish_query(wbuf, nwaves, k, a.partial + (q0 + j) * a.cand_cap, a.cand_cnt + q0 + j, a.done_cnt + q0 + j,
+                 gridDim.y, a.ids + (q0 + j) * a.out_stride, a.dist ? a.dist + (q0 + j) * a.out_stride : nullptr,
+                 &s_total, &s_off, &bv->last);
     __syncthreads();
   }
 }
@@ -1926,6 +1972,30 @@ void scan_chunks(int Q, int64_t max_rows, int64_t* nchunks_out, int64_t* chunk_r
   *chunk_rows_out = chunk_rows;
 }
 
+// Launch shape of the batched kernel k_scan_w4 for Q queries over `rows` rows: groups of four
+// queries (the last may be short) times row chunks.  Returns false when the kernel does not
+// apply or would leave most of the chip idle (then the one-query kernels split the rows).
+bool plan_batch(int M, int Q, int64_t rows, int topk, int64_t* nchunks_out, int64_t* chunk_rows_out) {
+  *nchunks_out = 1;
+  *chunk_rows_out = rows;
+  if (!rot_m(M) || topk > kWaveK4 || Q < 4 || rows < 1) return false;
+  const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
+  const int64_t groups = (Q + 3) / 4;
+  int64_t chunk_rows = (rows + tile - 1) / tile * tile, nchunks = 1;
+  if (groups < 2 * kWantBlocks) {  // fewer than two full rounds of blocks from the groups alone
+    const int64_t want = (kBatchWantBlocks + groups - 1) / groups;
+    const int64_t most = std::max<int64_t>(1, rows / (kBatchMinTiles * tile));
+    nchunks = std::min<int64_t>(std::min(want, most), 65535);
+    chunk_rows = (rows + nchunks - 1) / nchunks;
+    chunk_rows = (chunk_rows + tile - 1) / tile * tile;
+    nchunks = (rows + chunk_rows - 1) / chunk_rows;
+  }
+  if (groups * nchunks < kWantBlocks) return false;
+  *nchunks_out = nchunks;
+  *chunk_rows_out = chunk_rows;
+  return true;
+}
+
 // Scan `nrows_max` rows per query (linear: the whole array) and leave per-block partial keys in
 // the workspace; then select.  Workspace layout: [tau Q u32][partial Q*nchunks*k u64].
 int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const float* lut, int Q, int mode,
@@ -1953,7 +2023,10 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   a.codes = codes; a.N = N; a.M = M; a.lut = lut;
   a.target_ids = target_ids; a.target_offsets = target_offsets;
   a.chunk_rows = chunk_rows; a.k = topk; a.partial = partial; a.tau_g = tau;
-  a.cand_cnt = cand_cnt; a.cand_cap = nchunks * topk;
+  int64_t bchunks, brows;
+  const bool batched = plan_batch(M, Q, max_rows, topk, &bchunks, &brows) && mode == kLinear && !qmode;
+  a.cand_cnt = cand_cnt; a.cand_cap = std::max(nchunks, bchunks) * topk;
+  a.nq = Q;
   a.done_cnt = done_cnt; a.ids = ids; a.dist = dist; a.out_stride = out_stride;
   a.qmode = qmode; a.want_mode = want_mode;
   dim3 grid((unsigned)nchunks, (unsigned)Q);
@@ -1967,15 +2040,39 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     const int pre_blocks = (int)std::min<int64_t>(kPrepassBlocks, (max_rows + tile_rows - 1) / tile_rows);
     const bool prepass = nchunks > 1;
     ScanArgs pre = a;
-    pre.minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * nchunks * topk);
+    pre.minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * a.cand_cap);
     pre.counter = pre_counter;
     dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
     const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
-    if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2) {
-      // Large batch, every block owns its queries' whole scan: four queries per block with the
-      // half-precision filter (k_scan_w4) when topk allows, then two per block (k_scan_w2) and a
-      // single one (k_scan_w) for what is left.  Later groups are addressed as query 0.. of
-      // argument arrays shifted by the number of queries already launched.
+    const size_t lds4 = 65536 + 4 * (size_t)(kScanThreads / 64 + 1) * kWaveCap4 * 8 +
+                        (size_t)(kScanThreads / 64) * kRescoreCap * 8 + kBlockVarsBytes;
+    const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
+    if (batched) {
+      // Four queries per block with the half-precision filter; the rows are cut into chunks
+      // when the groups alone would not fill the chip, and then the bound-seeding pass runs
+      // first so that no block starts without a bound.
+      ScanArgs a4 = a;
+      a4.chunk_rows = brows;
+      const dim3 g4((unsigned)((Q + 3) / 4), (unsigned)bchunks);
+      const bool pre4 = bchunks > 1;
+      switch (M) {
+        case 8: { int rc = set_lds0(k_scan_w4<8>, lds4); if (rc) return rc;
+                  if (pre4) { rc = set_lds0(k_tau0<8, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
+                              k_tau0<8, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
+                  k_scan_w4<8><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+        case 16: { int rc = set_lds0(k_scan_w4<16>, lds4); if (rc) return rc;
+                   if (pre4) { rc = set_lds0(k_tau0<16, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
+                               k_tau0<16, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
+                   k_scan_w4<16><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+        default: { int rc = set_lds0(k_scan_w4<32>, lds4); if (rc) return rc;
+                   if (pre4) { rc = set_lds0(k_tau0<32, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
+                               k_tau0<32, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
+                   k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+      }
+    } else if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2) {
+      // Large batch with topk beyond the four-query kernel's reach: two queries per block
+      // (k_scan_w2), every block owning its queries' whole scan, and a single-query block for an
+      // odd one left over, addressed as query 0 of argument arrays shifted by Q - 1.
       auto shifted = [&](int o) {
         ScanArgs b = a;
         b.lut = lut + (size_t)o * M * 256;
@@ -1985,37 +2082,17 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
         b.dist = dist ? dist + (size_t)o * out_stride : nullptr;
         return b;
       };
-      const size_t lds4 = 65536 + 4 * (size_t)(kScanThreads / 64 + 1) * kWaveCap4 * 8 +
-                          (size_t)(kScanThreads / 64) * kRescoreCap * 8 + kBlockVarsBytes;
-      const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
-      int done = 0;
-      if (topk <= kWaveK4 && Q >= 4) {
-        dim3 g4(1, (unsigned)(Q / 4));
-        switch (M) {
-          case 8: { int rc = set_lds0(k_scan_w4<8>, lds4); if (rc) return rc;
-                    k_scan_w4<8><<<g4, kScanThreads, lds4, st>>>(a); } break;
-          case 16: { int rc = set_lds0(k_scan_w4<16>, lds4); if (rc) return rc;
-                     k_scan_w4<16><<<g4, kScanThreads, lds4, st>>>(a); } break;
-          default: { int rc = set_lds0(k_scan_w4<32>, lds4); if (rc) return rc;
-                     k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a); } break;
-        }
-        done = Q / 4 * 4;
+      const dim3 g2(1, (unsigned)(Q / 2));
+      switch (M) {
+        case 8: { int rc = set_lds0(k_scan_w2<8>, lds2); if (rc) return rc;
+                  k_scan_w2<8><<<g2, kScanThreads, lds2, st>>>(a); } break;
+        case 16: { int rc = set_lds0(k_scan_w2<16>, lds2); if (rc) return rc;
+                   k_scan_w2<16><<<g2, kScanThreads, lds2, st>>>(a); } break;
+        default: { int rc = set_lds0(k_scan_w2<32>, lds2); if (rc) return rc;
+                   k_scan_w2<32><<<g2, kScanThreads, lds2, st>>>(a); } break;
       }
-      if (Q - done >= 2) {
-        ScanArgs b = shifted(done);
-        dim3 g2(1, (unsigned)((Q - done) / 2));
-        switch (M) {
-          case 8: { int rc = set_lds0(k_scan_w2<8>, lds2); if (rc) return rc;
-                    k_scan_w2<8><<<g2, kScanThreads, lds2, st>>>(b); } break;
-          case 16: { int rc = set_lds0(k_scan_w2<16>, lds2); if (rc) return rc;
-                     k_scan_w2<16><<<g2, kScanThreads, lds2, st>>>(b); } break;
-          default: { int rc = set_lds0(k_scan_w2<32>, lds2); if (rc) return rc;
-                     k_scan_w2<32><<<g2, kScanThreads, lds2, st>>>(b); } break;
-        }
-        done += (Q - done) / 2 * 2;
-      }
-      if (Q - done == 1) {
-        ScanArgs b = shifted(done);
+      if (Q & 1) {
+        ScanArgs b = shifted(Q - 1);
         switch (M) {
           case 8: { int rc = set_lds0(k_scan_w<8, kLinear>, ldsw); if (rc) return rc;
                     k_scan_w<8, kLinear><<<dim3(1, 1), kScanThreads, ldsw, st>>>(b); } break;
@@ -2049,7 +2126,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_stop), st));
   if (topk > kWaveK) {
     SelectArgs s{};
-    s.keys = partial; s.nkeys = nchunks * topk; s.key_cnt = cand_cnt; s.k = topk; s.out_stride = out_stride;
+    s.keys = partial; s.nkeys = a.cand_cap; s.key_cnt = cand_cnt; s.k = topk; s.out_stride = out_stride;
     s.ids = ids; s.dist = dist; s.qmode = qmode; s.want_mode = want_mode;
     k_select<<<Q, kScanThreads, 0, st>>>(s);
   }
@@ -2057,9 +2134,12 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   return RII_OK;
 }
 
-size_t scan_ws_bytes(int Q, int64_t max_rows, int topk) {
+size_t scan_ws_bytes(int M, int Q, int64_t max_rows, int topk) {
   int64_t nchunks, chunk_rows;
   scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
+  int64_t bchunks, brows;
+  plan_batch(M, Q, max_rows, topk, &bchunks, &brows);
+  nchunks = std::max(nchunks, bchunks);
   return 4 * align_up((size_t)Q * 4, 256) + (size_t)Q * nchunks * topk * 8 +
          (size_t)Q * kPrepassBlocks * (kScanThreads / 64) * 4 + 256;
 }
@@ -2083,7 +2163,7 @@ int rii_adc_scan_linear(const rii_index_t* idx, const float* lut, int Q, int top
   if (!idx || !lut || !ids || !dist || Q < 1 || topk < 1) return RII_ERR_INVALID_ARG;
   if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
   if (idx->N < 1) return RII_ERR_INVALID_ARG;
-  int rc = ensure_ws(idx, scan_ws_bytes(Q, idx->N, topk));
+  int rc = ensure_ws(idx, scan_ws_bytes(idx->M, Q, idx->N, topk));
   if (rc) return rc;
   return launch_scan(idx, idx->d_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
                      nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
@@ -2098,7 +2178,7 @@ int rii_adc_scan_subset(const rii_index_t* idx, const float* lut, int Q, const i
   if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
   if (max_targets > idx->N) max_targets = idx->N;
   int64_t rows = std::max<int64_t>(max_targets, 1);
-  int rc = ensure_ws(idx, scan_ws_bytes(Q, rows, topk));
+  int rc = ensure_ws(idx, scan_ws_bytes(idx->M, Q, rows, topk));
   if (rc) return rc;
   return launch_scan(idx, idx->d_codes, idx->N, lut, Q, kSubset, target_ids, target_offsets, rows, topk, ids, dist,
                      topk, nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
@@ -2126,7 +2206,7 @@ int rii_topk(const float* cand_dist, const int32_t* cand_ids, const int64_t* can
 
 // coarse ranking into caller buffers; `ws` must hold what coarse_ws_bytes() says
 static size_t coarse_ws_bytes(const rii_index* idx, int Q, int nprobe) {
-  if (nprobe <= RII_MAX_TOPK) return scan_ws_bytes(Q, idx->K, nprobe);
+  if (nprobe <= RII_MAX_TOPK) return scan_ws_bytes(idx->M, Q, idx->K, nprobe);
   return align_up((size_t)Q * idx->K * 4, 256) + align_up((size_t)(Q + 1) * 8, 256);
 }
 
@@ -2260,7 +2340,7 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
   const size_t lut_b = align_up((size_t)Q * M * 256 * 4, 256);
   const size_t plan_b = align_up((size_t)Q * 4, 256);
   const size_t probe_b = align_up((size_t)Q * pmax * 4, 256);
-  const size_t scan_b = align_up(scan_ws_bytes(Q, lin_rows, topk), 256);
+  const size_t scan_b = align_up(scan_ws_bytes(idx->M, Q, lin_rows, topk), 256);
   const size_t coarse_b = has_lists ? align_up(coarse_ws_bytes(idx, Q, pmax), 256) : 0;
   int rc = ensure_ws(idx, lut_b + 2 * plan_b + probe_b + std::max(scan_b, coarse_b));
   if (rc) return rc;

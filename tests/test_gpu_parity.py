@@ -126,6 +126,33 @@ def test_linear_scan_ties_and_padding(rii, oracle_lib):
         check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
 
 
+@pytest.mark.parametrize("M,Q,topk", [(8, 263, 100), (16, 258, 10)])
+def test_linear_scan_large_batch_in_row_chunks(M, Q, topk, rii, oracle_lib):
+    """A batch that takes the several-queries-per-block kernel, over a code array long enough to
+    be cut into row chunks; Q is not a multiple of four (short last group).  Codes are uniform
+    bytes; copies of row 5 sit on both sides of every fifth tile boundary (the chunks here come
+    out 65 tiles long, so every chunk boundary has them) and query 0 is row 5's own
+    reconstruction, so its top-100 is a run of exact ties that crosses several chunks."""
+    N = 2 * 2097152 + 3 * 4096 + 77
+    rng = np.random.default_rng(11 + M)
+    cb = rng.normal(size=(M, 256, 2)).astype(np.float32)
+    codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+    for b in range(4096, N, 4096 * 5):
+        codes[b - 1:b + 1] = codes[5]
+    q = rng.normal(size=(Q, 2 * M)).astype(np.float32)
+    q[0] = np.concatenate([cb[m][codes[5][m]] for m in range(M)])
+    index = rii.Index(cb)
+    index.add(codes)
+    lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+    ids, dist = rii.rii_adc_scan_linear(index, lut, topk)
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    A = oracle_lib.lut(cb, q)
+    for i in range(Q):
+        ref = oracle_lib.linear_scan(A[i], codes, topk)
+        assert np.array_equal(ids[i], ref[0]) and np.array_equal(dist[i], ref[1]), f"query {i}"
+
+
 def test_generic_m(rii, oracle_lib):
     """M = 12 takes the run-time-M code path."""
     d = make_index(rii, oracle_lib, N=9000, D=48, M=12, K=0, seed=7, Q=5)
