@@ -456,6 +456,7 @@ __device__ __forceinline__ void write_result(const uint64_t* keys, int c, int k,
 // the waves' sorted buffers are merged by the block.
 constexpr int kWaveK = 128;
 constexpr int kWaveCap = 256;
+constexpr int kUnitTiles = 8;  // wave-tiles per unit of rows taken by a wave of k_scan_w
 
 // Cross-block hand-over without cache-wide fences: the data is written with agent-scope
 // atomic stores (which go through to the coherence point), the writer waits for its own stores
@@ -799,54 +800,80 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
     nrows = a.target_offsets[q + 1] - o0;
     tids = a.target_ids + o0;
   }
-  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
-  const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
-  const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
   uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
   const int k = a.k;
+  const float* lut = a.lut + q * M * 256;
 
-  if (r0 < r1) {  // block-uniform
-    const float* lut = a.lut + q * M * 256;
-    if constexpr (rot_m(MT)) {
+  if constexpr (rot_m(MT)) {
+    // Rotated stored form.  Every block has its share of the rows (a.chunk_rows of them), cut
+    // into units of kUnitTiles wave-tiles (a wave-tile = 64 lanes x kRowsPerLane consecutive
+    // 64-row slices); the block's waves take the units in turn, so each wave streams runs of
+    // kUnitTiles * 256 consecutive rows and no wave waits for another inside the loop.
+    // (Handing the units out through counters, so that fast blocks take work from slow ones,
+    // was measured slower: the wait for a counter's value drains the wave's load pipeline.)
+    if (nrows > 0) {  // block-uniform
+      // The query's shared bound is re-read once per tile by the block's first wave only and
+      // passed on through LDS (a plain word, read without synchronisation: a stale value is
+      // still a valid bound); thousands of waves polling one address would serialise on it.
+      // Its first value is in place before the barriers of the table fill, hence before any
+      // wave can read it.
+      uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), lut);  // the wave buffers are not in use yet
-    } else {
-      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
-      __syncthreads();
-    }
-    int cnt = 0;
-    uint32_t tau = kOrdMax;
-    // The query's shared bound is re-read once per tile by the block's first wave only and
-    // passed on through LDS (a plain word, read without synchronisation: a stale value is
-    // still a valid bound); thousands of waves polling one address would serialise on it.
-    uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    // Software pipeline over the tiles (rotated form): the code words of tile t+1 are requested
-    // while tile t is scored.  Per row, all LDS addresses are formed first; the row's words are
-    // dead from then on and their registers receive the next tile's row before the look-ups
-    // start.  Row numbers past the chunk's end are clamped to its last row (valid memory) and
-    // masked when they are scored; the ids of a target list run one more tile ahead.
-    auto id_at = [&](int64_t tile, int r) -> int32_t {
-      int64_t i = tile + (int64_t)r * blockDim.x + tid;
-      if (i >= r1) i = r1 - 1;
-      return MODE == kLinear ? (int32_t)i : tids[i];
-    };
-    [[maybe_unused]] int32_t rid[kRowsPerLane], rid_n[kRowsPerLane];
-    [[maybe_unused]] uint32_t w[kRowsPerLane][rot_m(MT) ? MT / 4 : 1];
-    if constexpr (rot_m(MT)) {
+      constexpr int64_t kWaveTile = 64 * kRowsPerLane;
+      constexpr int64_t kUnitRows = kUnitTiles * kWaveTile;
+      // this block's share (a.chunk_rows is a multiple of the unit; the last share may be short or empty)
+      const int64_t share_lo = (int64_t)blockIdx.x * a.chunk_rows;
+      const int64_t share_n = share_lo >= nrows ? 0 : (nrows - share_lo < a.chunk_rows ? nrows - share_lo : a.chunk_rows);
+      const uint32_t share_units = (uint32_t)((share_n + kUnitRows - 1) / kUnitRows);
+      uint32_t my_next = (uint32_t)wave;
+      // first row of the next unit for this wave, -1 when its part of the share is used up (wave-uniform)
+      auto next_unit = [&]() -> int64_t {
+        if (my_next >= share_units) return -1;
+        const uint32_t u = my_next;
+        my_next += (uint32_t)nwaves;
+        return share_lo + (int64_t)u * kUnitRows;
+      };
+      int64_t unit_base = next_unit();
+      int t_in = 0;
+      // first row of the next wave-tile of this wave, -1 when the rows are used up
+      auto next_tile = [&]() -> int64_t {
+        if (unit_base < 0) return -1;
+        const int64_t base = unit_base + (int64_t)t_in * kWaveTile;
+        if (++t_in == kUnitTiles) {
+          t_in = 0;
+          unit_base = next_unit();
+        }
+        return base < nrows ? base : -1;
+      };
+      // row (linear) or target (subset) number of slice r of the tile at `base`, clamped to
+      // the last one (valid memory; such rows are masked when scored), and its identifier
+      auto id_at = [&](int64_t base, int r) -> int32_t {
+        int64_t i = base < 0 ? nrows - 1 : base + r * 64 + lane;
+        if (i >= nrows) i = nrows - 1;
+        return MODE == kLinear ? (int32_t)i : tids[i];
+      };
+      int cnt = 0;
+      uint32_t tau = kOrdMax;
+      // Software pipeline over the wave's tiles: the code words of the next tile are requested
+      // while the current one is scored.  Per slice, all LDS addresses are formed first; the
+      // slice's words are dead from then on and their registers receive the next tile's slice
+      // before the look-ups start.  The identifiers of a target list run one more tile ahead.
+      int64_t b0 = next_tile(), b1 = next_tile(), b2 = next_tile();
+      int32_t rid[kRowsPerLane], rid_n[kRowsPerLane];
+      uint32_t w[kRowsPerLane][MT / 4];
 #pragma unroll
-      for (int r = 0; r < kRowsPerLane; ++r) rid[r] = id_at(r0, r);
+      for (int r = 0; r < kRowsPerLane; ++r) rid[r] = id_at(b0, r);
 #pragma unroll
       for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + (int64_t)rid[r] * M, w[r]);
 #pragma unroll
-      for (int r = 0; r < kRowsPerLane; ++r) rid_n[r] = id_at(r0 + tile_step, r);
-    }
-    for (int64_t tile = r0; tile < r1; tile += tile_step) {
-      uint64_t key[kRowsPerLane];
-      uint32_t pend = 0;
-      uint32_t fresh = kOrdMax;
-      if (wave == 0) fresh = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const uint32_t bound = tg < tau ? tg : tau;
-      if constexpr (rot_m(MT)) {
+      for (int r = 0; r < kRowsPerLane; ++r) rid_n[r] = id_at(b1, r);
+      while (b0 >= 0) {  // wave-uniform
+        uint64_t key[kRowsPerLane];
+        uint32_t pend = 0;
+        uint32_t fresh = kOrdMax;
+        if (wave == 0) fresh = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t bound = tg < tau ? tg : tau;
         // filter on the conflict-free rotated-order sum; exact ascending-m sum for the few rows that pass
         const float fb = rot_filter(bound, rot_eps(MT));
         int32_t rid_nn[kRowsPerLane];
@@ -854,8 +881,8 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
           key[r] = kKeyMax;
-          if (tile + (int64_t)r * blockDim.x + tid < r1) live |= 1u << r;
-          rid_nn[r] = id_at(tile + 2 * tile_step, r);
+          if (b0 + r * 64 + lane < nrows) live |= 1u << r;
+          rid_nn[r] = id_at(b2, r);
         }
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
@@ -875,12 +902,45 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
             }
           }
         }
+        if (__ballot(pend != 0) != 0ull) {
+          const uint32_t before = tau;
+          wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
+          if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
+        }
+        if (tid == 0) __hip_atomic_store(&s_tg, fresh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        tg = __hip_atomic_load(&s_tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        b0 = b1; b1 = b2; b2 = next_tile();
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
           rid[r] = rid_n[r];
           rid_n[r] = rid_nn[r];
         }
-      } else {
+      }
+      tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // the block's own k best go to the query's candidate list
+      const uint32_t bound = tg < tau ? tg : tau;
+      uint64_t* best;
+      const int c = block_collect(wbuf, nwaves, cnt, tau, bound, k, &best, &s_total, &s_off);
+      publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
+    }
+  } else {
+    // Plain stored form (other M): every block takes a fixed share of the rows.
+    const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
+    const int64_t r0 = (int64_t)blockIdx.x * a.chunk_rows;
+    const int64_t r1 = r0 + a.chunk_rows < nrows ? r0 + a.chunk_rows : nrows;
+    if (r0 < r1) {  // block-uniform
+      uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
+      __syncthreads();  // also orders the first value of s_tg before any wave reads it
+      int cnt = 0;
+      uint32_t tau = kOrdMax;
+      for (int64_t tile = r0; tile < r1; tile += tile_step) {
+        uint64_t key[kRowsPerLane];
+        uint32_t pend = 0;
+        uint32_t fresh = kOrdMax;
+        if (wave == 0) fresh = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t bound = tg < tau ? tg : tau;
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
           // a wave owns 64 consecutive rows of each of the tile's kRowsPerLane slices
@@ -893,21 +953,20 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
             if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
           }
         }
+        if (__ballot(pend != 0) != 0ull) {
+          const uint32_t before = tau;
+          wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
+          if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
+        }
+        if (tid == 0) __hip_atomic_store(&s_tg, fresh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        tg = __hip_atomic_load(&s_tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
-      if (__ballot(pend != 0) != 0ull) {
-        const uint32_t before = tau;
-        wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
-        if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
-      }
-      if (tid == 0) __hip_atomic_store(&s_tg, fresh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      tg = __hip_atomic_load(&s_tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t bound = tg < tau ? tg : tau;
+      uint64_t* best;
+      const int c = block_collect(wbuf, nwaves, cnt, tau, bound, k, &best, &s_total, &s_off);
+      publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
     }
-    tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // the block's own k best go to the query's candidate list
-    const uint32_t bound = tg < tau ? tg : tau;
-    uint64_t* best;
-    const int c = block_collect(wbuf, nwaves, cnt, tau, bound, k, &best, &s_total, &s_off);
-    publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
   }
   finish_query(wbuf, nwaves, k, cand, a.cand_cnt + q, a.done_cnt + q, gridDim.x, a.ids + q * a.out_stride,
                a.dist ? a.dist + q * a.out_stride : nullptr, &s_total, &s_off, &s_last);
@@ -1620,14 +1679,14 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
 }
 
 // ------------------------------------------------------------------ small utility kernels
-// tau[q] = largest bound; the three counter arrays that follow it (stride entries apart) = 0
+// tau[q] = largest bound; the kScanArrays - 1 counter arrays that follow it (stride entries apart) = 0
+constexpr int kScanArrays = 4;
 __global__ void k_init_scan(uint32_t* tau, int Q, int stride) {
-  int q = blockIdx.x * blockDim.x + threadIdx.x;
-  if (q >= Q) return;
-  tau[q] = kOrdMax;
-  tau[stride + q] = 0u;
-  tau[2 * (size_t)stride + q] = 0u;
-  tau[3 * (size_t)stride + q] = 0u;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Q) return;
+  tau[i] = kOrdMax;
+#pragma unroll
+  for (int j = 1; j < kScanArrays; ++j) tau[j * (size_t)stride + i] = 0u;
 }
 
 // Per-query plan of the query procedure (Alg. 3): mode 0 = linear scan, 1 = inverted index;
@@ -2016,9 +2075,8 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   uint32_t* cand_cnt = tau + cstride;
   uint32_t* pre_counter = tau + 2 * cstride;
   uint32_t* done_cnt = tau + 3 * cstride;
-  uint64_t* partial = reinterpret_cast<uint64_t*>(base + 4 * cstride * 4);
+  uint64_t* partial = reinterpret_cast<uint64_t*>(base + kScanArrays * cstride * 4);
 
-  k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
   ScanArgs a{};
   a.codes = codes; a.N = N; a.M = M; a.lut = lut;
   a.target_ids = target_ids; a.target_offsets = target_offsets;
@@ -2027,6 +2085,9 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   const bool batched = plan_batch(M, Q, max_rows, topk, &bchunks, &brows) && mode == kLinear && !qmode;
   a.cand_cnt = cand_cnt; a.cand_cap = std::max(nchunks, bchunks) * topk;
   a.nq = Q;
+  // [prepass minima] follow the candidates
+  uint32_t* minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * a.cand_cap);
+  k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
   a.done_cnt = done_cnt; a.ids = ids; a.dist = dist; a.out_stride = out_stride;
   a.qmode = qmode; a.want_mode = want_mode;
   dim3 grid((unsigned)nchunks, (unsigned)Q);
@@ -2040,7 +2101,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     const int pre_blocks = (int)std::min<int64_t>(kPrepassBlocks, (max_rows + tile_rows - 1) / tile_rows);
     const bool prepass = nchunks > 1;
     ScanArgs pre = a;
-    pre.minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * a.cand_cap);
+    pre.minima = minima;
     pre.counter = pre_counter;
     dim3 pgrid((unsigned)pre_blocks, (unsigned)Q);
     const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
@@ -2139,8 +2200,8 @@ size_t scan_ws_bytes(int M, int Q, int64_t max_rows, int topk) {
   scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
   int64_t bchunks, brows;
   plan_batch(M, Q, max_rows, topk, &bchunks, &brows);
-  nchunks = std::max(nchunks, bchunks);
-  return 4 * align_up((size_t)Q * 4, 256) + (size_t)Q * nchunks * topk * 8 +
+  const int64_t cap_chunks = std::max(nchunks, bchunks);
+  return kScanArrays * align_up((size_t)Q * 4, 256) + (size_t)Q * cap_chunks * topk * 8 +
          (size_t)Q * kPrepassBlocks * (kScanThreads / 64) * 4 + 256;
 }
 
@@ -2257,7 +2318,7 @@ static int ivf_split(int Q, int nprobe) {
 }
 
 static size_t ivf_ws_bytes(int Q, int nprobe, int topk) {
-  return 4 * align_up((size_t)Q * 4, 256) + (size_t)Q * ivf_split(Q, nprobe) * topk * 8 + 256;
+  return kScanArrays * align_up((size_t)Q * 4, 256) + (size_t)Q * ivf_split(Q, nprobe) * topk * 8 + 256;
 }
 
 static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32_t* probe, int probe_stride,
@@ -2276,7 +2337,7 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
     const size_t cstride = align_up((size_t)Q * 4, 256) / 4;
     uint32_t* tau = static_cast<uint32_t*>(ws);
     a.tau_g = tau; a.cand_cnt = tau + cstride; a.done_cnt = tau + 3 * cstride;
-    a.cand = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(ws) + 4 * cstride * 4);
+    a.cand = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(ws) + kScanArrays * cstride * 4);
     a.cand_cap = (int64_t)split * topk;
     k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
     const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
