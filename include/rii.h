@@ -229,6 +229,20 @@ int rii_rotate(const float* R, int D, const float* x, int64_t n, float* y, void*
 int rii_assign(const rii_index_t* index, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,
                int32_t* assign_out, void* stream);
 
+/* ------------------------------------------------------------------ measurement -------- */
+
+/* LDS look-up ceiling of the scan kernels' inner loop, for the roofline of the batched scan
+ * (Sec. 3: a distance is M table look-ups; with several queries per pass these, not the code
+ * stream, bound the kernel).  Runs `blocks` blocks of 1024 threads; every lane performs
+ * iters * 32 dependent-free look-ups (one byte-permute, one LDS read of `width` bytes at a
+ * conflict-free pseudo-random address in a 64 KB table, one add per component) and nothing
+ * else; no global memory traffic inside the loop.
+ *   width 4 or 8 (ds_read_b32 / ds_read_b64); lds_bytes >= 65536 sizes the block's LDS
+ *   allocation (and thereby blocks per CU); sink device uint32 [1] (written only to keep the
+ *   loop alive).  The caller times the call with events on `stream`.
+ * Look-ups performed = blocks * 1024 * 32 * iters. */
+int rii_bench_lds_lookups(int width, int blocks, int iters, int lds_bytes, uint32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

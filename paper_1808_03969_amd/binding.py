@@ -310,6 +310,15 @@ def rii_assign(index: Index, codes: torch.Tensor, coarse: torch.Tensor) -> torch
     return out
 
 
+def rii_bench_lds_lookups(width: int, blocks: int, iters: int, lds_bytes: int = 98 * 1024) -> int:
+    """Measurement aid: launch the LDS look-up ceiling kernel on the current stream (time it with
+    events); returns the number of look-ups it performs."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    _check(load_library().rii_bench_lds_lookups(width, blocks, iters, lds_bytes, _dp(sink), _stream()),
+           "rii_bench_lds_lookups")
+    return blocks * 1024 * 32 * iters
+
+
 def rii_index_set_scan_events(index: Index, start_event, stop_event):
     """Measurement aid: raw hipEvent_t handles (ints or None) recorded around the linear-scan kernel."""
     s = ctypes.c_void_p(start_event) if start_event else None

@@ -273,6 +273,11 @@ __device__ __forceinline__ void load_row_words(const uint8_t* __restrict__ row, 
   }
 }
 
+// Look-ups after which k_scan_w tests whether a whole wavefront can abandon a slice (half-way
+// through the row; anywhere between 1/2 and 3/4 measured the same).  With four queries per
+// block (k_scan_w4) the test hardly ever succeeds and was measured to cost more than it saves.
+template <int MT> constexpr int kAbandonAt = MT / 2;
+
 // One segment of a stored row: kRotSeg<MT> bytes (16, or 8 for M = 8), as words.
 template <int MT> constexpr int kRotSeg = MT >= 16 ? 16 : 8;
 template <int MT>
@@ -316,6 +321,20 @@ __device__ __forceinline__ float rot_sum(const uint32_t (&addr)[MT]) {
   float d = 0.f;
 #pragma unroll
   for (int t = 0; t < MT; ++t) d = __fadd_rn(d, lds_read_f32(addr[t] + t * 4));
+  return d;
+}
+// The same with early abandoning: the entries are squared distances (>= 0) and adding one never
+// lowers a sum, so a partial sum above the filter bound fb settles the row; when that holds in
+// every lane the wave skips the remaining look-ups (the value returned is then only known to
+// exceed fb).
+template <int MT>
+__device__ __forceinline__ float rot_sum_abandon(const uint32_t (&addr)[MT], float fb) {
+  float d = 0.f;
+#pragma unroll
+  for (int t = 0; t < kAbandonAt<MT>; ++t) d = __fadd_rn(d, lds_read_f32(addr[t] + t * 4));
+  if (__ballot(d <= fb) == 0ull) return d;
+#pragma unroll
+  for (int t = kAbandonAt<MT>; t < MT; ++t) d = __fadd_rn(d, lds_read_f32(addr[t] + t * 4));
   return d;
 }
 
@@ -889,7 +908,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
           uint32_t addr[MT];
           rot_addrs<MT>(w[r], ((uint32_t)rid[r] & 31u) << 2, addr);
           load_row_words<MT>(a.codes + (int64_t)rid_n[r] * M, w[r]);
-          if (rot_sum<MT>(addr) <= fb) maybe |= 1u << r;
+          if (rot_sum_abandon<MT>(addr, fb) <= fb) maybe |= 1u << r;
         }
         maybe &= live;
         if (__ballot(maybe != 0) != 0ull) {
@@ -1986,6 +2005,15 @@ int set_lds(Kern kern, size_t bytes) {
   return RII_OK;
 }
 
+// The kernels that address their table as "LDS address 0" must not have static LDS in front of
+// the dynamic allocation; refuse to launch otherwise.
+template <typename Kern>
+int require_table_at_lds_zero(Kern kern) {
+  hipFuncAttributes attr{};
+  RII_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
+  return attr.sharedSizeBytes == 0 ? RII_OK : RII_ERR_DEVICE;
+}
+
 // set_lds for the kernels whose table must sit at LDS address 0 (checked once per kernel)
 template <typename Kern>
 int set_lds0(Kern kern, size_t bytes) {
@@ -1998,15 +2026,6 @@ int set_lds0(Kern kern, size_t bytes) {
     which = reinterpret_cast<const void*>(kern);
   }
   return set_lds(kern, bytes);
-}
-
-// The kernels that address their table as "LDS address 0" must not have static LDS in front of
-// the dynamic allocation; refuse to launch otherwise.
-template <typename Kern>
-int require_table_at_lds_zero(Kern kern) {
-  hipFuncAttributes attr{};
-  RII_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
-  return attr.sharedSizeBytes == 0 ? RII_OK : RII_ERR_DEVICE;
 }
 
 #define DISPATCH_M(M, ...)                                  \
@@ -2205,6 +2224,50 @@ size_t scan_ws_bytes(int M, int Q, int64_t max_rows, int topk) {
          (size_t)Q * kPrepassBlocks * (kScanThreads / 64) * 4 + 256;
 }
 
+// ------------------------------------------------------------------ LDS look-up ceiling
+// The inner loop of the scan kernels with everything else taken away: per look-up one byte
+// permute (address), one LDS read, one add per component.  The "code words" are made up in
+// registers (a xorshift step per 32 look-ups); lane l uses slot (l + t) % 32 at step t like
+// k_scan_w2 / k_scan_w4, so the 32 lanes of a half-wave never share a bank.
+template <int WIDTH>
+__global__ __launch_bounds__(kScanThreads) void k_lds_lookups(int iters, uint32_t* sink) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 65536 / 4; i += blockDim.x) reinterpret_cast<uint32_t*>(smem)[i] = (uint32_t)i;
+  __syncthreads();
+  uint32_t lb4[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    lb4[j] = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) lb4[j] |= ((uint32_t)((tid + 4 * j + b) & 31) * 8u) << (8 * b);
+  }
+  uint32_t w[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) w[j] = (uint32_t)(tid * 8 + j) * 2654435761u + blockIdx.x;
+  uint32_t acc0 = 0, acc1 = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int t = 0; t < 32; ++t) {
+      const uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lb4[t >> 2], 0x0c0c0400u | ((uint32_t)(t & 3) * 0x0101u));
+      if constexpr (WIDTH == 8) {
+        uint2 v = lds_read_u32x2(addr);
+        acc0 += v.x;
+        acc1 += v.y;
+      } else {
+        acc0 += __float_as_uint(lds_read_f32(addr & ~4u));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      w[j] ^= w[j] << 13;
+      w[j] ^= w[j] >> 17;
+      w[j] ^= w[j] << 5;
+    }
+  }
+  if ((acc0 ^ acc1) == 0x9e3779b9u) sink[0] = acc0;  // practically never: keeps the loop alive
+}
+
 }  // namespace
 
 // ====================================================================== entry points
@@ -2215,6 +2278,23 @@ int rii_build_lut(const rii_index_t* idx, const float* q, int Q, float* lut, voi
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   hipStream_t st = static_cast<hipStream_t>(stream);
   k_build_lut<<<dim3(idx->M, Q), 256, 0, st>>>(idx->d_cb, q, idx->D, idx->M, idx->Ds, lut);
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_bench_lds_lookups(int width, int blocks, int iters, int lds_bytes, uint32_t* sink, void* stream) {
+  if ((width != 4 && width != 8) || blocks < 1 || iters < 1 || !sink) return RII_ERR_INVALID_ARG;
+  if (lds_bytes < 65536 || lds_bytes > 160 * 1024) return RII_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (width == 8) {
+    int rc = set_lds0(k_lds_lookups<8>, (size_t)lds_bytes);
+    if (rc) return rc;
+    k_lds_lookups<8><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
+  } else {
+    int rc = set_lds0(k_lds_lookups<4>, (size_t)lds_bytes);
+    if (rc) return rc;
+    k_lds_lookups<4><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
+  }
   RII_HIP(hipGetLastError());
   return RII_OK;
 }
