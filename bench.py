@@ -11,9 +11,12 @@ on), with every input already resident in HBM:
     -> subset (gathered) scan + top-R -> the Alg. 3 query procedure on the whole database.
 
 It prints ONE JSON line.  `value` is the number of PQ codes scored per second over the whole
-step; `roofline` is the linear-scan kernel (algorithmic bytes M per code and query pass,
-timed with HIP events recorded around that kernel inside the timed steps); `cpu_baseline` is the
-CPU oracle's linear scan timed single-threaded on a bounded sample of the same codes.
+step.  `roofline` is the one-query-per-pass linear scan (k_tau0 + k_scan_w: M algorithmic bytes
+per code, bound by HBM), timed with HIP events recorded around those kernels on their stream;
+`roofline_batched` is the batched launch of the timed steps (k_scan_w4: four queries share each
+code byte, so the bound is the LDS look-up rate; its ceiling is measured live with the library's
+look-up-only kernel).  `cpu_baseline` is the CPU oracle's linear scan timed single-threaded on a
+bounded sample of the same codes.
 """
 from __future__ import annotations
 
@@ -30,10 +33,22 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the batched linear-scan kernel, from the rocprofv3 PMC runs summarised in
-# profiles/k_scan_w_c5_hbm_traffic_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated
-# with a plain streaming kernel).  Reported only for the exact configuration it was measured on.
-MEASURED_TRAFFIC = {("c5_billion_shard", 100_000_000, 10_000): 5_277_510_390 * 2.0 * 1024 + 56_996 * 1024}
+# HBM-side bytes per launch from the rocprofv3 PMC runs summarised in
+# profiles/k_scan_w_k_scan_w4_c5_hbm_traffic_pmc.txt (FETCH_SIZE
+# x 2.000 + WRITE_SIZE x 1.000 KiB, the factors found with a plain streaming kernel of known
+# size).  Reported only for the exact configuration they were measured on.
+MEASURED_TRAFFIC = {
+    ("c5_billion_shard", 100_000_000, 10_000): {
+        # k_tau0 + k_scan_w, one query: (16,577 + 1,563,614) KiB fetched x 2, (136 + 98) KiB written
+        "single": (16_577 + 1_563_614) * 2.0 * 1024 + (136 + 98) * 1024,
+        # k_scan_w4, 10,000 queries: 2,817,086,371 KiB fetched x 2, 8,127 KiB written
+        "batched": 2_817_086_371 * 2.0 * 1024 + 8_127 * 1024,
+    },
+}
+
+# LDS look-up ceiling from unit counts: 256 CUs x 128 B/clk of LDS bandwidth at 2.4 GHz; an
+# 8-byte look-up (ds_read_b64) therefore at most 16 lanes per clock and CU.
+LDS_SPEC_LOOKUPS_PER_S = 256 * 16 * 2.4e9
 
 
 def log(*a):
@@ -162,17 +177,41 @@ def main():
     single_ms = float(np.mean(single[2:]))
 
     scan_avg_ms = float(np.mean(scan_ms))
-    alg_bytes = float(Q) * N * M          # M bytes per code and query pass
-    achieved = alg_bytes / (scan_avg_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get((cfg.name, N, Q), {})
+    single_gbs = N * M / (single_ms * 1e-3) / 1e9   # M algorithmic bytes per code and query pass
     roofline = {
-        "bound": "hbm", "kernel": f"k_scan_w4<{M}> (batched launch) / k_scan_w<{M},linear> (single query)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC.get((cfg.name, N, Q)),
-        "launch_ms": round(scan_avg_ms, 3), "algorithmic_bytes_per_launch": alg_bytes,
-        "single_query_pass": {"launch_ms": round(single_ms, 4), "achieved": round(N * M / (single_ms * 1e-3) / 1e9, 1),
-                              "frac": round(N * M / (single_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                              "codes_per_s": round(N / (single_ms * 1e-3), 1)},
+        "bound": "hbm", "kernel": f"k_tau0<{M},linear> + k_scan_w<{M},linear>, one query per launch",
+        "achieved": round(single_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(single_gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get("single"),
+        "launch_ms": round(single_ms, 4), "algorithmic_bytes_per_launch": float(N) * M,
+        "codes_per_s": round(N / (single_ms * 1e-3), 1),
     }
+    # The batched launch: look-ups, not bytes, are what bounds it.
+    batched = None
+    from paper_1808_03969_amd import binding
+    qpb, row_chunks = binding.rii_scan_linear_plan(index, Q, R)
+    if qpb == 4:
+        groups = (Q + 3) // 4
+        lookups = float(groups) * N * M            # one 8-byte LDS read per code byte and group of four queries
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ceil_ms = []
+        for _ in range(4):
+            a.record()
+            n_lk = binding.rii_bench_lds_lookups(8, 256, 4000, 150 * 1024)   # one block per CU, as k_scan_w4 runs
+            b.record()
+            torch.cuda.synchronize()
+            ceil_ms.append(a.elapsed_time(b))
+        ceiling = n_lk / (min(ceil_ms[1:]) * 1e-3)
+        ach = lookups / (scan_avg_ms * 1e-3)
+        batched = {
+            "bound": "lds", "kernel": f"k_scan_w4<{M}>, {Q} queries per launch, {row_chunks} row chunk(s)", "achieved": round(ach / 1e9, 1),
+            "peak": round(ceiling / 1e9, 1), "unit": "G look-ups/s", "frac": round(ach / ceiling, 4),
+            "peak_source": "measured live: rii_bench_lds_lookups(width 8, 256 blocks x 1024 threads)",
+            "spec_peak": round(LDS_SPEC_LOOKUPS_PER_S / 1e9, 1), "frac_of_spec": round(ach / LDS_SPEC_LOOKUPS_PER_S, 4),
+            "traffic": traffic.get("batched"), "launch_ms": round(scan_avg_ms, 3),
+            "algorithmic_bytes_per_launch": float(Q) * N * M,
+            "algorithmic_gbs": round(float(Q) * N * M / (scan_avg_ms * 1e-3) / 1e9, 1),
+        }
 
     if args.pmc_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
@@ -219,6 +258,7 @@ def main():
         "codes_scored_per_step": scored,
         "hbm_frac_of_peak": roofline["frac"],
         "roofline": roofline,
+        "roofline_batched": batched,
         "cpu_baseline": cpu,
         "index": {"paper_bytes": info["paper_bytes"], "device_bytes": info["device_bytes"], "setup_s": w["timings"]},
     }

@@ -231,6 +231,12 @@ int rii_assign(const rii_index_t* index, const uint8_t* codes, int64_t n, const 
 
 /* ------------------------------------------------------------------ measurement -------- */
 
+/* Launch shape rii_adc_scan_linear uses for a batch of Q queries on this index (so that a
+ * benchmark can name the kernel it timed): *queries_per_block = 4, 2 or 1 queries sharing one
+ * pass over the codes (Alg. 1 run for several queries at once; results are per query);
+ * *row_chunks = blocks that share one query group's rows.  Host call, no GPU work. */
+int rii_scan_linear_plan(const rii_index_t* index, int Q, int topk, int* queries_per_block, int64_t* row_chunks);
+
 /* LDS look-up ceiling of the scan kernels' inner loop, for the roofline of the batched scan
  * (Sec. 3: a distance is M table look-ups; with several queries per pass these, not the code
  * stream, bound the kernel).  Runs `blocks` blocks of 1024 threads; every lane performs

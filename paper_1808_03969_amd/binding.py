@@ -310,6 +310,14 @@ def rii_assign(index: Index, codes: torch.Tensor, coarse: torch.Tensor) -> torch
     return out
 
 
+def rii_scan_linear_plan(index: Index, Q: int, topk: int):
+    """(queries per block, row chunks per query group) of the launch rii_adc_scan_linear would make."""
+    qpb, chunks = ctypes.c_int(0), ctypes.c_int64(0)
+    _check(load_library().rii_scan_linear_plan(index.handle, Q, topk, ctypes.byref(qpb), ctypes.byref(chunks)),
+           "rii_scan_linear_plan")
+    return qpb.value, chunks.value
+
+
 def rii_bench_lds_lookups(width: int, blocks: int, iters: int, lds_bytes: int = 98 * 1024) -> int:
     """Measurement aid: launch the LDS look-up ceiling kernel on the current stream (time it with
     events); returns the number of look-ups it performs."""

@@ -2282,6 +2282,24 @@ int rii_build_lut(const rii_index_t* idx, const float* q, int Q, float* lut, voi
   return RII_OK;
 }
 
+int rii_scan_linear_plan(const rii_index_t* idx, int Q, int topk, int* queries_per_block, int64_t* row_chunks) {
+  if (!idx || !queries_per_block || !row_chunks || Q < 1 || topk < 1) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
+  int64_t nchunks, chunk_rows, bchunks, brows;
+  scan_chunks(Q, idx->N, &nchunks, &chunk_rows);
+  if (topk <= kWaveK && plan_batch(idx->M, Q, idx->N, topk, &bchunks, &brows)) {
+    *queries_per_block = 4;
+    *row_chunks = bchunks;
+  } else if (topk <= kWaveK && rot_m(idx->M) && nchunks == 1 && Q >= 2) {
+    *queries_per_block = 2;
+    *row_chunks = 1;
+  } else {
+    *queries_per_block = 1;
+    *row_chunks = nchunks;
+  }
+  return RII_OK;
+}
+
 int rii_bench_lds_lookups(int width, int blocks, int iters, int lds_bytes, uint32_t* sink, void* stream) {
   if ((width != 4 && width != 8) || blocks < 1 || iters < 1 || !sink) return RII_ERR_INVALID_ARG;
   if (lds_bytes < 65536 || lds_bytes > 160 * 1024) return RII_ERR_INVALID_ARG;
