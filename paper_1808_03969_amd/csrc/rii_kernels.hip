@@ -1616,10 +1616,23 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
   write_result(keys, s_cnt, a.k, a.ids + q * a.k, a.dist ? a.dist + q * a.k : nullptr);
 }
 
-// Inverted-index scan without a candidate cap, split over several blocks per query: block b of
-// a query takes the probed lists b, b + gridDim.x, ... (the result of Alg. 2 does not depend on
-// the visiting order when all members of the probed lists are scored).  Selection per wavefront
-// as in k_scan_w; the blocks' results meet in the query's candidate list.
+// Inverted-index scan over the concatenation of a query's probed lists, for the two cases in
+// which Alg. 2's result does not depend on who scores which member: no candidate cap (every
+// member of the probed lists is a candidate), or a cap without a target set (the candidates are
+// then simply the first L members in traversal order).  The members are numbered 0 .. total-1
+// in traversal order ("virtual" positions; a prefix sum over the list lengths, kept in LDS, maps
+// them to positions in the list-ordered arrays), cut into units of kUnitTiles wave-tiles and dealt
+// to the waves of the query's blocks in turn -- tiles are full whatever the list lengths are.
+// Scoring, software pipeline and selection as in k_scan_w; identifiers are read for every
+// member only when a target set has to be tested, otherwise only for the few rows that pass the
+// distance filter.
+constexpr int kIvfMaxProbe = 4096;  // lists per query this kernel keeps prefix sums for
+
+__host__ __device__ inline size_t ivf_w_lds(int M, int nprobe) {
+  return table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + (size_t)(2 * nprobe + 2) * 4 +
+         kBlockVarsBytes;
+}
+
 template <int MT>
 __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
   extern __shared__ __align__(16) uint8_t smem[];
@@ -1628,55 +1641,172 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
   uint64_t* wbuf = reinterpret_cast<uint64_t*>(smem + table_bytes(M));  // [waves + 1][kWaveCap]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
-  BlockVars* bv = reinterpret_cast<BlockVars*>(wbuf + (size_t)(nwaves + 1) * kWaveCap);
+  uint32_t* s_pref = reinterpret_cast<uint32_t*>(wbuf + (size_t)(nwaves + 1) * kWaveCap);  // [nprobe + 1] (+1 pad)
+  uint32_t* s_start = s_pref + a.nprobe + 2;                                               // [nprobe]
+  BlockVars* bv = reinterpret_cast<BlockVars*>(s_start + a.nprobe);
   int& s_total = bv->total;
   int& s_off = bv->off;
   int& s_last = bv->last;
   const int64_t q = blockIdx.y;
+  if (a.qmode && a.qmode[q] != a.want_mode) return;
   uint64_t* cand = a.cand + q * a.cand_cap;
   const int k = a.k;
-  const int np = a.nprobe;
-  if ((int)blockIdx.x < np) {  // block-uniform: this block has at least one list
+  const int np = a.nprobe_q ? a.nprobe_q[q] : a.nprobe;
+
+  // list starts and the running total of list lengths (the lists are disjoint: the total is < 2^31)
+  for (int i = tid; i < np; i += blockDim.x) {
+    const int list = a.probe[q * a.probe_stride + i];
+    const int64_t b = a.list_off[list], e = a.list_off[list + 1];
+    s_start[i] = (uint32_t)b;
+    s_pref[i + 1] = (uint32_t)(e - b);
+  }
+  if (tid == 0) s_pref[0] = 0u;
+  __syncthreads();
+  if (wave == 0) {
+    const int per = (np + 63) / 64;
+    const int lo = lane * per < np ? lane * per : np, hi = lo + per < np ? lo + per : np;
+    uint32_t sum = 0;
+    for (int i = lo; i < hi; ++i) sum += s_pref[i + 1];
+    uint32_t incl = sum;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += t;
+    }
+    uint32_t run = incl - sum;
+    for (int i = lo; i < hi; ++i) {
+      run += s_pref[i + 1];
+      s_pref[i + 1] = run;
+    }
+  }
+  __syncthreads();
+  int64_t total = s_pref[np];
+  if (a.Lcap > 0 && total > a.Lcap) total = a.Lcap;  // (only launched without a target set then)
+
+  constexpr int64_t kWaveTile = 64 * kRowsPerLane;
+  constexpr int64_t kUnitRows = kUnitTiles * kWaveTile;
+  const int64_t nunits = (total + kUnitRows - 1) / kUnitRows;
+  if ((int64_t)blockIdx.x * nwaves < nunits) {  // block-uniform: at least one wave of this block has a unit
+    const float* lut = a.lut + q * M * 256;
     if constexpr (rot_m(MT)) {
-      fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), a.lut + q * M * 256);
+      fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), lut);  // the wave buffers are not in use yet
     } else {
-      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = a.lut[q * M * 256 + i];
+      for (int i = tid; i < M * 256; i += blockDim.x) A[i] = lut[i];
       __syncthreads();
     }
     const int32_t* S = nullptr;
     int64_t nS = 0;
     if (a.target_ids) {
-      int64_t o0 = a.target_offsets[q];
+      const int64_t o0 = a.target_offsets[q];
       S = a.target_ids + o0;
       nS = a.target_offsets[q + 1] - o0;
     }
     uint64_t* buf = wbuf + (size_t)wave * kWaveCap;
     int cnt = 0;
     uint32_t tau = kOrdMax;
-    for (int p = blockIdx.x; p < np; p += gridDim.x) {
-      const int list = a.probe[q * a.probe_stride + p];
-      const int64_t b = a.list_off[list], e = a.list_off[list + 1];
-      const uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      for (int64_t t0 = b; t0 < e; t0 += (int64_t)blockDim.x * kRowsPerLane) {
+    uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    int64_t unit = (int64_t)blockIdx.x * nwaves + wave;
+    const int64_t unit_step = (int64_t)gridDim.x * nwaves;
+    int t_in = 0;
+    int hint = 0;  // a list at or before the one the next tile starts in (wave-uniform)
+    // One tile of the wave: virtual base (or -1), positions of its kRowsPerLane slices in the
+    // list-ordered arrays (members past the end repeat the last one and are not live).
+    struct Tile { int64_t base; uint32_t pos[kRowsPerLane]; uint32_t live; };
+    auto next_tile = [&]() -> Tile {
+      Tile t;
+      t.live = 0;
+      if (unit >= nunits || unit * kUnitRows + (int64_t)t_in * kWaveTile >= total) {
+        t.base = -1;
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) t.pos[r] = s_start[0];  // any valid position (total > 0 here)
+        return t;
+      }
+      t.base = unit * kUnitRows + (int64_t)t_in * kWaveTile;
+      if (t_in == 0) {  // new unit: find the list of its first member, largest p with pref[p] <= base
+        int lo = 0, hi = np;  // pref[lo] <= base < pref[hi] (base < total <= pref[np])
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if ((int64_t)s_pref[mid] <= t.base) lo = mid;
+          else hi = mid;
+        }
+        hint = lo;
+      }
+      int p = hint;
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) {
+        int64_t v = t.base + r * 64 + lane;
+        if (v < total) t.live |= 1u << r;
+        else v = total - 1;
+        while ((int64_t)s_pref[p + 1] <= v) ++p;  // ends: v < total <= pref[np]
+        t.pos[r] = s_start[p] + (uint32_t)(v - (int64_t)s_pref[p]);
+      }
+      hint = __shfl(p, 63, 64);  // the last member's list: not after the next tile's first
+      if (++t_in == kUnitTiles) {
+        t_in = 0;
+        unit += unit_step;
+      }
+      return t;
+    };
+
+    if constexpr (rot_m(MT)) {
+      Tile cur = next_tile(), nxt = next_tile();
+      uint32_t w[kRowsPerLane][MT / 4];
+      int32_t idc[kRowsPerLane], idn[kRowsPerLane];
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) {
+        load_row_words<MT>(a.codes_list + (int64_t)cur.pos[r] * M, w[r]);
+        idc[r] = S ? a.list_ids[cur.pos[r]] : 0;
+      }
+      while (cur.base >= 0) {  // wave-uniform
         const uint32_t bound = tg < tau ? tg : tau;
-        const float fb = rot_filter(bound, rot_eps(M));
+        const float fb = rot_filter(bound, rot_eps(MT));
+        uint64_t key[kRowsPerLane];
+        uint32_t maybe = 0, pend = 0;
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+          key[r] = kKeyMax;
+          uint32_t addr[MT];
+          rot_addrs<MT>(w[r], (cur.pos[r] & 31u) << 2, addr);
+          load_row_words<MT>(a.codes_list + (int64_t)nxt.pos[r] * M, w[r]);
+          idn[r] = S ? a.list_ids[nxt.pos[r]] : 0;
+          if (rot_sum_abandon<MT>(addr, fb) <= fb) maybe |= 1u << r;
+        }
+        maybe &= cur.live;
+        if (__ballot(maybe != 0) != 0ull) {
+#pragma unroll
+          for (int r = 0; r < kRowsPerLane; ++r) {
+            if (maybe & (1u << r)) {
+              const int32_t id = S ? idc[r] : a.list_ids[cur.pos[r]];
+              if (S && !is_member(S, nS, id)) continue;
+              const float d = adc_row_exact_rot<MT>(A, a.codes_list + (int64_t)cur.pos[r] * M, cur.pos[r]);
+              key[r] = make_key(d, id);
+              if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
+            }
+          }
+        }
+        if (__ballot(pend != 0) != 0ull) {
+          const uint32_t before = tau;
+          wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
+          if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
+        }
+        cur = nxt;
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) idc[r] = idn[r];
+        if (t_in == 0) tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        nxt = next_tile();
+      }
+    } else {
+      for (Tile cur = next_tile(); cur.base >= 0; cur = next_tile()) {
+        const uint32_t bound = tg < tau ? tg : tau;
         uint64_t key[kRowsPerLane];
         uint32_t pend = 0;
 #pragma unroll
         for (int r = 0; r < kRowsPerLane; ++r) {
-          const int64_t pos = t0 + (int64_t)r * blockDim.x + tid;
           key[r] = kKeyMax;
-          if (pos < e) {
-            const int32_t id = a.list_ids[pos];
+          if (cur.live & (1u << r)) {
+            const int32_t id = a.list_ids[cur.pos[r]];
             if (S && !is_member(S, nS, id)) continue;
-            float d;
-            if constexpr (rot_m(MT)) {
-              d = adc_row_rot<MT>(A, a.codes_list + pos * M, ((uint32_t)pos & 31u) << 2);
-              if (!(d <= fb)) continue;
-              d = adc_row_exact_rot<MT>(A, a.codes_list + pos * M, pos);
-            } else {
-              d = adc_row<MT>(A, a.codes_list + pos * M, M);
-            }
+            const float d = adc_row<MT>(A, a.codes_list + (int64_t)cur.pos[r] * M, M);
             key[r] = make_key(d, id);
             if ((uint32_t)(key[r] >> 32) <= bound) pend |= 1u << r;
           }
@@ -1686,9 +1816,10 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
           wave_offer<kRowsPerLane>(buf, cnt, tau, k, key, pend, lane);
           if (tau < before && lane == 0) atomicMin(a.tau_g + q, tau);
         }
+        if (t_in == 0) tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-    const uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint64_t* best;
     const int c = block_collect(wbuf, nwaves, cnt, tau, tg < tau ? tg : tau, k, &best, &s_total, &s_off);
     publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
@@ -2429,8 +2560,9 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
   a.lut = lut; a.probe = probe; a.probe_stride = probe_stride; a.nprobe = nprobe; a.nprobe_q = nprobe_q;
   a.target_ids = target_ids; a.target_offsets = target_offsets; a.Lcap = L; a.k = topk;
   a.ids = ids; a.dist = dist; a.qmode = qmode; a.want_mode = want_mode;
-  if (L == 0 && topk <= kWaveK && !nprobe_q && !qmode && ws && Q <= 65535) {
-    // no candidate cap: any visiting order gives the same result, so split the lists over blocks
+  if ((L == 0 || !target_ids) && topk <= kWaveK && nprobe <= kIvfMaxProbe && ws && Q <= 65535) {
+    // no candidate cap, or a cap without a target set: who scores which member does not matter,
+    // so the members of the probed lists are dealt to the waves of one or more blocks per query
     const int split = ivf_split(Q, nprobe);
     const size_t cstride = align_up((size_t)Q * 4, 256) / 4;
     uint32_t* tau = static_cast<uint32_t*>(ws);
@@ -2438,7 +2570,7 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
     a.cand = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(ws) + kScanArrays * cstride * 4);
     a.cand_cap = (int64_t)split * topk;
     k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
-    const size_t ldsw = table_bytes(M) + (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
+    const size_t ldsw = ivf_w_lds(M, nprobe);
     dim3 grid((unsigned)split, (unsigned)Q);
     DISPATCH_M(M, { int rc = set_lds0(k_ivf_w<MT>, ldsw); if (rc) return rc;
                     k_ivf_w<MT><<<grid, kScanThreads, ldsw, st>>>(a); });
@@ -2461,7 +2593,7 @@ int rii_adc_scan_ivf(const rii_index_t* idx, const float* lut, int Q, const int3
   if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
   if (topk > RII_MAX_TOPK || !m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
   void* ws = nullptr;
-  if (L == 0 && topk <= kWaveK) {
+  if ((L == 0 || !target_ids) && topk <= kWaveK) {
     int rc = ensure_ws(idx, ivf_ws_bytes(Q, nprobe, topk));
     if (rc) return rc;
     ws = idx->ws;
@@ -2481,10 +2613,10 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
   const int M = idx->M, K = idx->K;
   const bool has_lists = K > 0;
   // Largest number of lists any inverted-index query of this batch can ask for: such a query
-  // has |S| >= max(theta, 1).
+  // has |S| >= max(theta, 1), and |S| = N when there is no target set.
   int pmax = 1;
   if (has_lists) {
-    int64_t smin = std::max<int64_t>(idx->theta, 1);
+    int64_t smin = target_ids ? std::max<int64_t>(idx->theta, 1) : idx->N;
     int64_t p = ((int64_t)K * L + smin - 1) / smin;
     pmax = (int)std::min<int64_t>(p, K);
     if (pmax > RII_MAX_TOPK && K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
@@ -2501,7 +2633,8 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
   const size_t probe_b = align_up((size_t)Q * pmax * 4, 256);
   const size_t scan_b = align_up(scan_ws_bytes(idx->M, Q, lin_rows, topk), 256);
   const size_t coarse_b = has_lists ? align_up(coarse_ws_bytes(idx, Q, pmax), 256) : 0;
-  int rc = ensure_ws(idx, lut_b + 2 * plan_b + probe_b + std::max(scan_b, coarse_b));
+  const size_t ivf_b = has_lists && topk <= kWaveK ? align_up(ivf_ws_bytes(Q, pmax, topk), 256) : 0;
+  int rc = ensure_ws(idx, lut_b + 2 * plan_b + probe_b + std::max(std::max(scan_b, coarse_b), ivf_b));
   if (rc) return rc;
   uint8_t* w = static_cast<uint8_t*>(idx->ws);
   float* lut = reinterpret_cast<float*>(w); w += lut_b;
@@ -2526,7 +2659,7 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
     rc = coarse_rank(idx, lut, Q, pmax, probe, nullptr, pmax, qmode, 1, stage_ws, st);
     if (rc) return rc;
     rc = launch_ivf(idx, lut, Q, probe, pmax, pmax, nprobe_q, target_ids, target_offsets, L, topk, ids, dist, qmode,
-                    1, nullptr, st);
+                    1, ivf_b ? stage_ws : nullptr, st);
     if (rc) return rc;
   }
   RII_HIP(hipGetLastError());

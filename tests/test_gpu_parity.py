@@ -245,6 +245,37 @@ def test_ivf_scan(name, rii, oracle_lib, request):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+@pytest.mark.parametrize("M", [12, 8])
+def test_ivf_scan_short_and_empty_lists(M, rii, oracle_lib):
+    """Many short posting lists, some of them empty (more coarse centres than distinct nearest
+    ones), probed in every combination of target set and candidate cap; M = 12 takes the
+    run-time-M code path.  The cap cuts inside a list, lies beyond all members, or is 1."""
+    d = make_index(rii, oracle_lib, N=5000, D=48, M=M, K=700, seed=9, Q=7)
+    N, K, Q = d["N"], d["K"], len(d["q"])
+    # every seventh centre becomes a copy of centre 0: ties go to the smaller index, so the copies' lists are empty
+    d["coarse"][1::7] = d["coarse"][0]
+    d["a"] = oracle_lib.assign(d["T"], d["codes"], d["coarse"])
+    d["off"], d["lids"] = oracle_lib.build_lists(d["a"], K)
+    d["index"].set_lists(d["coarse"], d["off"], d["lids"])
+    assert (np.diff(d["off"]) == 0).sum() >= 90
+    lut = lut_dev(rii, d)
+    tids, toff = synth.subset_batch(81, N, [N // 2] * Q)
+    tids_d, toff_d = tids.cuda(), toff.cuda()
+    tids, toff = t2n(tids), t2n(toff)
+    for P in (1, 40, K):
+        probe, _ = rii.rii_coarse_assign(d["index"], lut, P)
+        for use_S, L in ((False, 0), (True, 0), (False, 1), (False, 333), (False, 10 * N), (True, 57)):
+            ids, dist = rii.rii_adc_scan_ivf(d["index"], lut, probe, 20,
+                                             target_ids=tids_d if use_S else None,
+                                             target_offsets=toff_d if use_S else None, L=L)
+            torch.cuda.synchronize()
+            for i in range(Q):
+                S = tids[toff[i]:toff[i + 1]] if use_S else None
+                ref = oracle_lib.inverted_index(d["lut_ref"][i], d["codes"], d["coarse"], d["off"], d["lids"],
+                                                R=20, P=P, S=S, Lcap=L)
+                check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
 # ---------------------------------------------------------------- PartialSort + Take
 def test_topk_on_explicit_candidates(rii):
     g = torch.Generator().manual_seed(3)
