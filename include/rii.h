@@ -243,7 +243,8 @@ int rii_scan_linear_plan(const rii_index_t* index, int Q, int topk, int* queries
  * iters * 32 dependent-free look-ups (one byte-permute, one LDS read of `width` bytes at a
  * conflict-free pseudo-random address in a 64 KB table, one add per component) and nothing
  * else; no global memory traffic inside the loop.
- *   width 4 or 8 (ds_read_b32 / ds_read_b64); lds_bytes >= 65536 sizes the block's LDS
+ *   width 4 or 8 (ds_read_b32 / ds_read_b64 with 32-bit adds per component) or 64 (ds_read_b64
+ *   with one 64-bit integer add per look-up); lds_bytes >= 65536 sizes the block's LDS
  *   allocation (and thereby blocks per CU); sink device uint32 [1] (written only to keep the
  *   loop alive).  The caller times the call with events on `stream`.
  * Look-ups performed = blocks * 1024 * 32 * iters. */

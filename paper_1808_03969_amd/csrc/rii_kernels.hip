@@ -12,7 +12,6 @@
 // identifier) order, so selection is exact and deterministic including ties.
 
 #include <hip/hip_runtime.h>
-#include <hip/hip_fp16.h>
 
 #include <algorithm>
 #include <cstdio>
@@ -1140,17 +1139,23 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w2(ScanArgs a) {
 }
 
 // ------------------------------------------------------------------ four queries per pass
-// Same setting as k_scan_w2 (whole-database scan, large batch, M = 8, 16, 32), four queries per
-// block, with the table held in half precision: T4[z][s] for 32 slots, each entry four fp16 values
-// (one per query), so one 8-byte LDS read serves four look-ups, and the sums are formed with
-// packed fp16 additions.  The fp16 sum is only a FILTER.  Per query the table is scaled by a
-// power of two so that no sum can overflow; with h = fp16(a) per entry and fp16 additions the
-// computed sum is at most  S (1 + 2^-11)^M + 2 M 2^-25  for an exact (scaled) sum S, so a row whose
-// exact distance is within the bound always satisfies
-//     fp16 sum <= bound * scale * (1 + 1.1 M 2^-11) + M 2^-23 .
-// Rows that pass are re-scored from the fp32 table in global memory, in ascending sub-space
-// order; results are therefore exactly those of the fp32 kernels.  Each wave keeps one candidate
-// buffer of kWaveCap4 keys per query.
+// Same setting as k_scan_w2 (whole-database scan, M = 8, 16, 32), four queries per block, with the
+// table quantised to 15-bit integers: T4[z][s] for 32 slots, each entry four 16-bit fields (one
+// per query) in one 64-bit word, so one 8-byte LDS read serves four look-ups and ONE 64-bit
+// integer addition (v_lshl_add_u64, full rate) accumulates all four sums -- per code byte one
+// byte permute, one LDS read, one add.  The integer sum is only a FILTER:
+//   e(a) = min(cap, floor(a * scale)),  cap = 32767 / M,  scale = cap / (largest entry) (rounded
+//   down), so a field never exceeds 32767 and never carries into its neighbour;
+//   sum_m e(a_m) <= scale * (1 + 2^-24) * (real sum) <= scale * tau * (1 + (M + 2) 2^-24) for a
+//   row whose fp32 ascending-order distance is <= tau, so with
+//   fbq = floor(tau * scale * (1 + 1e-5)) + 1 (at most 32767) every such row has sum <= fbq.
+//   The test for the four queries is one 64-bit subtraction: with C holding 0x8000 + fbq_j in
+//   field j, C - sum has bit 15 of field j set exactly when sum_j <= fbq_j (every field of the
+//   difference stays >= 1, so no borrow crosses fields).
+// The filter lets through rows up to (M + 1) / scale above the bound (about 3 % of the largest
+// table entry at M = 32).  Rows that pass are re-scored from the fp32 table in global memory, in
+// ascending sub-space order; results are therefore exactly those of the fp32 kernels.  Each wave
+// keeps one candidate buffer of kWaveCap4 keys per query.
 // When the batch alone does not give the chip several rounds of blocks, the code array is cut
 // into row chunks (grid.y, see plan_batch) and the chunks' results meet in the per-query
 // candidate lists as in k_scan_w; k_tau0 seeds the bounds first.
@@ -1196,11 +1201,12 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
   const int64_t nrows = r0 + a.chunk_rows < a.N ? r0 + a.chunk_rows : a.N;  // end of this block's rows
   const bool chunked = gridDim.y > 1;
 
-  // tables: one query at a time through a staging copy (the buffer area), scaled, rounded to
-  // fp16 and written along diagonals (see fill_table_rot)
+  // tables: one query at a time through a staging copy (the buffer area), quantised and written
+  // along diagonals (see fill_table_rot)
+  constexpr uint32_t kCap = 32767u / MT;
   {
     float* stage = reinterpret_cast<float*>(wbuf);
-    __half* T4h = reinterpret_cast<__half*>(smem);
+    uint16_t* T4q = reinterpret_cast<uint16_t*>(smem);
     for (int j = 0; j < 4; ++j) {
       const float* lut = a.lut + qsrc(j) * MT * 256;
       float mx = 0.f;
@@ -1215,15 +1221,12 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
       if (tid == 0) {
         float m2 = 0.f;
         for (int w = 0; w < nwaves; ++w) m2 = fmaxf(m2, s_red[w]);
-        // largest power of two with MT * max * scale <= 16384 (no fp16 sum can reach 65504)
-        int e = 0;
-        if (m2 > 0.f) {
-          (void)frexpf(m2 * (float)MT, &e);  // m2 * MT = f * 2^e, f in [0.5, 1)
-          e = 14 - e;
-        }
-        if (e > 24) e = 24;    // keep tiny tables out of the fp32 exponent's far end
-        if (e < -120) e = -120;
-        s_scale[j] = ldexpf(1.f, e);
+        // cap / max, rounded down a little; a table of zeros (or a tiny one) gets scale 0:
+        // every entry quantises to 0 and every row goes to the exact re-scoring
+        float sc = 0.f;
+        if (m2 > 1e-30f) sc = __fmul_rn(__fdiv_rn((float)kCap, m2), 0.999999f);
+        if (!(sc < 1e30f)) sc = 0.f;
+        s_scale[j] = sc;
       }
       __syncthreads();
       const float sc = s_scale[j];
@@ -1231,7 +1234,8 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
         const int l = it & 31, blk = it >> 5;
         const int s0 = blk & 31, z0 = (blk >> 5) << 5;
         const int z = z0 + l, s = (s0 + l) & 31;
-        T4h[(size_t)(z * 32 + s) * 4 + j] = __float2half_rn(stage[(s & (MT - 1)) * 256 + z] * sc);
+        uint32_t e = (uint32_t)floorf(__fmul_rn(stage[(s & (MT - 1)) * 256 + z], sc));
+        T4q[(size_t)(z * 32 + s) * 4 + j] = (uint16_t)(e < kCap ? e : kCap);
       }
       __syncthreads();
     }
@@ -1247,8 +1251,6 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
     for (int b = 0; b < 4; ++b) lb4[j] |= ((uint32_t)((tid + 4 * j + b) & 31) * 8u) << (8 * b);
   }
   const float scale0 = s_scale[0], scale1 = s_scale[1], scale2 = s_scale[2], scale3 = s_scale[3];
-  const float rel = 1.f + 1.1f * (float)MT * 4.8828125e-4f;   // 1 + 1.1 M 2^-11
-  const float slack = (float)MT * 1.1920929e-7f;               // M 2^-23
 
   int cnt[4] = {0, 0, 0, 0};
   uint32_t tau[4] = {kOrdMax, kOrdMax, kOrdMax, kOrdMax};
@@ -1290,23 +1292,30 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
 #pragma unroll
   for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(r0, r) * MT, w[r]);
   for (int64_t tile = r0; tile < nrows; tile += tile_step) {
-    float fb[4];
+    // C: field j = 0x8000 + fbq_j, fbq_j the filter bound of query j in its table's units
+    uint64_t C = 0;
     const float scl[4] = {scale0, scale1, scale2, scale3};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t bound = tau[j] < tg[j] ? tau[j] : tg[j];
-      fb[j] = bound == kOrdMax ? __uint_as_float(0x7F800000u) : float_of_ord(bound) * scl[j] * rel + slack;
+      uint32_t fbq = 32767u;
+      if (bound != kOrdMax) {
+        const float x = __fmul_rn(__fmul_rn(float_of_ord(bound), scl[j]), 1.00001f);
+        if (x < 32766.f) fbq = (uint32_t)x + 1u;  // x >= 0: distances are sums of squares
+      }
+      C |= (uint64_t)(0x8000u | fbq) << (16 * j);
     }
     uint32_t maybe[4] = {0, 0, 0, 0};
     // software pipeline as in k_scan_w, in segments of 16 code bytes: a segment's LDS addresses
     // first, then the request for the same segment of the next tile's row into the registers
     // just freed, then the look-ups
     uint32_t live = 0;
+    uint32_t plo[kRowsPerLane], phi[kRowsPerLane];
 #pragma unroll
     for (int r = 0; r < kRowsPerLane; ++r) {
       if (tile + (int64_t)r * blockDim.x + tid < nrows) live |= 1u << r;
       const uint8_t* next_row = a.codes + row_at(tile + tile_step, r) * MT;
-      __half2 acc01 = __float2half2_rn(0.f), acc23 = __float2half2_rn(0.f);
+      uint64_t acc = 0;
 #pragma unroll
       for (int sg = 0; sg < MT / kRotSeg<MT>; ++sg) {
         uint32_t addr[kRotSeg<MT>];
@@ -1318,18 +1327,29 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
         load_row_segment<MT>(next_row, sg, w[r]);
 #pragma unroll
         for (int u = 0; u < kRotSeg<MT>; ++u) {
-          uint2 v = lds_read_u32x2(addr[u]);  // T4 is at LDS address 0
-          acc01 = __hadd2(acc01, *reinterpret_cast<const __half2*>(&v.x));
-          acc23 = __hadd2(acc23, *reinterpret_cast<const __half2*>(&v.y));
+          const uint2 v = lds_read_u32x2(addr[u]);  // T4 is at LDS address 0
+          acc += ((uint64_t)v.y << 32) | v.x;       // four 16-bit sums at once
         }
       }
-      if (__low2float(acc01) <= fb[0]) maybe[0] |= 1u << r;
-      if (__high2float(acc01) <= fb[1]) maybe[1] |= 1u << r;
-      if (__low2float(acc23) <= fb[2]) maybe[2] |= 1u << r;
-      if (__high2float(acc23) <= fb[3]) maybe[3] |= 1u << r;
+      const uint64_t pass = (C - acc) & 0x8000800080008000ull;
+      plo[r] = (uint32_t)pass;
+      phi[r] = (uint32_t)(pass >> 32);
     }
+    uint32_t any = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) maybe[j] = j < nlive ? maybe[j] & live : 0u;
+    for (int r = 0; r < kRowsPerLane; ++r) any |= (live >> r) & 1u ? (plo[r] | phi[r]) : 0u;
+    if (__ballot(any != 0) != 0ull) {  // rare: unpack the pass bits per query
+#pragma unroll
+      for (int r = 0; r < kRowsPerLane; ++r) {
+        if (!((live >> r) & 1u)) continue;
+        if (plo[r] & 0x00008000u) maybe[0] |= 1u << r;
+        if (plo[r] & 0x80000000u) maybe[1] |= 1u << r;
+        if (phi[r] & 0x00008000u) maybe[2] |= 1u << r;
+        if (phi[r] & 0x80000000u) maybe[3] |= 1u << r;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) maybe[j] = j < nlive ? maybe[j] : 0u;
+    }
     // Rows that pass a filter are not re-scored on the spot (one or two lanes busy, the wave
     // waiting on their table reads from global memory) but queued as (query, row); a full
     // wavefront of 64 queued entries is then re-scored at once, one entry per lane.
@@ -2259,7 +2279,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
                         (size_t)(kScanThreads / 64) * kRescoreCap * 8 + kBlockVarsBytes;
     const size_t lds2 = 65536 + 2 * (size_t)(kScanThreads / 64 + 1) * kWaveCap * 8 + kBlockVarsBytes;
     if (batched) {
-      // Four queries per block with the half-precision filter; the rows are cut into chunks
+      // Four queries per block with the integer-table filter; the rows are cut into chunks
       // when the groups alone would not fill the chip, and then the bound-seeding pass runs
       // first so that no block starts without a bound.
       ScanArgs a4 = a;
@@ -2377,11 +2397,15 @@ __global__ __launch_bounds__(kScanThreads) void k_lds_lookups(int iters, uint32_
 #pragma unroll
   for (int j = 0; j < 8; ++j) w[j] = (uint32_t)(tid * 8 + j) * 2654435761u + blockIdx.x;
   uint32_t acc0 = 0, acc1 = 0;
+  uint64_t acc64 = 0;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int t = 0; t < 32; ++t) {
       const uint32_t addr = __builtin_amdgcn_perm(w[t >> 2], lb4[t >> 2], 0x0c0c0400u | ((uint32_t)(t & 3) * 0x0101u));
-      if constexpr (WIDTH == 8) {
+      if constexpr (WIDTH == 64) {
+        uint2 v = lds_read_u32x2(addr);
+        acc64 += ((uint64_t)v.y << 32) | v.x;  // one 64-bit integer add per look-up
+      } else if constexpr (WIDTH == 8) {
         uint2 v = lds_read_u32x2(addr);
         acc0 += v.x;
         acc1 += v.y;
@@ -2396,6 +2420,7 @@ __global__ __launch_bounds__(kScanThreads) void k_lds_lookups(int iters, uint32_
       w[j] ^= w[j] << 5;
     }
   }
+  acc0 ^= (uint32_t)acc64 ^ (uint32_t)(acc64 >> 32);
   if ((acc0 ^ acc1) == 0x9e3779b9u) sink[0] = acc0;  // practically never: keeps the loop alive
 }
 
@@ -2432,10 +2457,14 @@ int rii_scan_linear_plan(const rii_index_t* idx, int Q, int topk, int* queries_p
 }
 
 int rii_bench_lds_lookups(int width, int blocks, int iters, int lds_bytes, uint32_t* sink, void* stream) {
-  if ((width != 4 && width != 8) || blocks < 1 || iters < 1 || !sink) return RII_ERR_INVALID_ARG;
+  if ((width != 4 && width != 8 && width != 64) || blocks < 1 || iters < 1 || !sink) return RII_ERR_INVALID_ARG;
   if (lds_bytes < 65536 || lds_bytes > 160 * 1024) return RII_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (width == 8) {
+  if (width == 64) {
+    int rc = set_lds0(k_lds_lookups<64>, (size_t)lds_bytes);
+    if (rc) return rc;
+    k_lds_lookups<64><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
+  } else if (width == 8) {
     int rc = set_lds0(k_lds_lookups<8>, (size_t)lds_bytes);
     if (rc) return rc;
     k_lds_lookups<8><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
