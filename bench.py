@@ -11,8 +11,8 @@ on), with every input already resident in HBM:
     -> subset (gathered) scan + top-R -> the Alg. 3 query procedure on the whole database.
 
 It prints ONE JSON line.  `value` is the number of PQ codes scored per second over the whole
-step.  `roofline` is the one-query-per-pass linear scan (k_tau0 + k_scan_w: M algorithmic bytes
-per code, bound by HBM), timed with HIP events recorded around those kernels on their stream;
+step.  `roofline` is the one-query-per-pass linear scan (k_scan_w: M algorithmic bytes per code, bound
+by HBM), timed with HIP events recorded around that kernel on its stream;
 `roofline_batched` is the batched launch of the timed steps (k_scan_w4: four queries share each
 code byte, so the bound is the LDS look-up rate; its ceiling is measured live with the library's
 look-up-only kernel).  `cpu_baseline` is the CPU oracle's linear scan timed single-threaded on a
@@ -180,7 +180,7 @@ def main():
     traffic = MEASURED_TRAFFIC.get((cfg.name, N, Q), {})
     single_gbs = N * M / (single_ms * 1e-3) / 1e9   # M algorithmic bytes per code and query pass
     roofline = {
-        "bound": "hbm", "kernel": f"k_tau0<{M},linear> + k_scan_w<{M},linear>, one query per launch",
+        "bound": "hbm", "kernel": f"k_scan_w<{M},linear> (seeds its bound itself), one query per launch",
         "achieved": round(single_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(single_gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get("single"),
         "launch_ms": round(single_ms, 4), "algorithmic_bytes_per_launch": float(N) * M,

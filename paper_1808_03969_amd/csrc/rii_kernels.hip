@@ -392,6 +392,7 @@ struct ScanArgs {
   uint32_t* minima;              // bound-seeding pass: [Q][gridDim.x * waves] smallest distance image per wave
   uint32_t* counter;             // bound-seeding pass: [Q] blocks finished
   int nq;                        // k_scan_w4: queries in the batch (the last group may be short)
+  int seed_inside;               // k_scan_w: seed the shared bound inside the kernel (see there)
 };
 
 enum { kLinear = 0, kSubset = 1 };
@@ -475,6 +476,8 @@ __device__ __forceinline__ void write_result(const uint64_t* keys, int c, int k,
 constexpr int kWaveK = 128;
 constexpr int kWaveCap = 256;
 constexpr int kUnitTiles = 8;  // wave-tiles per unit of rows taken by a wave of k_scan_w
+constexpr uint32_t kSeedReady = 1u << 20;    // added to a query's counter once its seeded bound is in tau_g
+constexpr long long kSeedWaitTicks = 5000;   // longest wait for that, in ticks of the 100 MHz clock (50 us)
 
 // Cross-block hand-over without cache-wide fences: the data is written with agent-scope
 // atomic stores (which go through to the coherence point), the writer waits for its own stores
@@ -886,6 +889,76 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
       for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + (int64_t)rid[r] * M, w[r]);
 #pragma unroll
       for (int r = 0; r < kRowsPerLane; ++r) rid_n[r] = id_at(b1, r);
+      if (a.seed_inside) {  // block-uniform (a launch parameter)
+        // Bound seeding without a kernel of its own (used when all blocks of the launch are
+        // resident at once and a query has at least k of them).  Every block scores the first
+        // tile of each of its waves and records the smallest distance among those rows; the
+        // k-th smallest of the blocks' minima belongs to k different rows, so it bounds the k-th
+        // smallest distance of the whole scan from above.  The block that arrives last selects
+        // it, stores it in tau_g and raises the query's counter by kSeedReady; the others wait
+        // for that -- for at most kSeedWaitTicks of the 100 MHz clock, after which they go on
+        // with whatever bound there is (the bound only saves work, results do not depend on it).
+        uint32_t best = kOrdMax;
+        if (b0 >= 0) {
+#pragma unroll
+          for (int r = 0; r < kRowsPerLane; ++r) {
+            uint32_t addr[MT];
+            rot_addrs<MT>(w[r], ((uint32_t)rid[r] & 31u) << 2, addr);
+            float d = rot_sum<MT>(addr);
+            d = __fadd_rn(d, __fmul_rn(d, rot_eps(MT)));  // not below the row's ascending-m sum
+            const uint32_t o = ord_of(d);
+            if (b0 + r * 64 + lane < nrows && o < best) best = o;
+          }
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+          const uint32_t other = __shfl_xor(best, o, 64);
+          if (other < best) best = other;
+        }
+        uint32_t* s_min = reinterpret_cast<uint32_t*>(bv->red);  // [waves]
+        if (lane == 0) s_min[wave] = best;
+        __syncthreads();
+        if (tid == 0) {
+          for (int i = 1; i < nwaves; ++i) best = s_min[i] < best ? s_min[i] : best;
+          __hip_atomic_store(a.minima + q * gridDim.x + blockIdx.x, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          wait_own_memory_ops();
+          s_last = (atomicAdd(a.counter + q, 1u) & (kSeedReady - 1u)) == gridDim.x - 1;
+        }
+        __syncthreads();
+        if (s_last && wave == 0) {
+          // k-th smallest of the gridDim.x <= 256 minima, most significant bit first
+          uint32_t v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int i = lane + 64 * j;
+            v[j] = i < (int)gridDim.x
+                       ? __hip_atomic_load(a.minima + q * gridDim.x + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                       : kOrdMax;
+          }
+          uint32_t ans = 0;
+          for (int b = 31; b >= 0; --b) {
+            const uint32_t trial = ans | (1u << b);
+            int c = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c += v[j] < trial;
+            for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+            if (c < k) ans = trial;
+          }
+          if (lane == 0) {
+            if (ans != kOrdMax) atomicMin(a.tau_g + q, ans);
+            wait_own_memory_ops();
+            atomicAdd(a.counter + q, kSeedReady);
+          }
+        }
+        if (tid == 0) {
+          const long long t0 = wall_clock64();
+          while (__hip_atomic_load(a.counter + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < kSeedReady &&
+                 wall_clock64() - t0 < kSeedWaitTicks)
+            __builtin_amdgcn_s_sleep(16);
+        }
+        __syncthreads();
+        tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
       while (b0 >= 0) {  // wave-uniform
         uint64_t key[kRowsPerLane];
         uint32_t pend = 0;
@@ -2269,7 +2342,14 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
     // rows seeds the shared bound, so that the main pass starts with few candidates.
     const int64_t tile_rows = (int64_t)kScanThreads * kRowsPerLane;
     const int pre_blocks = (int)std::min<int64_t>(kPrepassBlocks, (max_rows + tile_rows - 1) / tile_rows);
-    const bool prepass = nchunks > 1;
+    // The single-query kernel seeds the bound itself when all its blocks run at once and a query
+    // has at least topk of them (rotated form only); otherwise a separate pass does it.
+    const bool seed_inside = nchunks > 1 && rot_m(M) && !batched && nchunks >= topk && nchunks <= kPrepassBlocks &&
+                             (int64_t)Q * nchunks <= kWantBlocks;
+    const bool prepass = nchunks > 1 && !seed_inside;
+    a.seed_inside = seed_inside ? 1 : 0;
+    a.minima = minima;
+    a.counter = pre_counter;
     ScanArgs pre = a;
     pre.minima = minima;
     pre.counter = pre_counter;
