@@ -101,6 +101,29 @@ def test_linear_scan(name, topk, rii, oracle_lib, request):
         assert np.array_equal(dist[i], ref[1])  # same additions in the same order
 
 
+@pytest.mark.parametrize("M", [8, 32])
+def test_linear_scan_one_to_three_queries(M, rii, oracle_lib):
+    """Fewer than four queries take the one-query-per-block kernel with the rows split over
+    blocks (18 per query here).  With topk <= 18 the kernel seeds the shared bound itself, above
+    that the separate seeding pass runs; both sides of that switch and every batch size 1..3."""
+    N = 300001
+    rng = np.random.default_rng(21 + M)
+    cb = rng.normal(size=(M, 256, 2)).astype(np.float32)
+    codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+    q = rng.normal(size=(3, 2 * M)).astype(np.float32)
+    index = rii.Index(cb)
+    index.add(codes)
+    lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+    A = oracle_lib.lut(cb, q)
+    for Q in (1, 2, 3):
+        for topk in (1, 5, 18, 19, 100, 128):
+            ids, dist = rii.rii_adc_scan_linear(index, lut[:Q].contiguous(), topk)
+            torch.cuda.synchronize()
+            for i in range(Q):
+                ref = oracle_lib.linear_scan(A[i], codes, topk)
+                assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), (Q, topk, i)
+
+
 def test_linear_scan_ties_and_padding(rii, oracle_lib):
     """Many identical codes (exact distance ties) and fewer rows than topk."""
     rng = np.random.default_rng(5)
