@@ -48,6 +48,7 @@ static_assert(sizeof(BlockVars) <= kBlockVarsBytes, "BlockVars must fit its slot
 
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kOrdMax = 0xFFFFFFFFu;
+constexpr uint32_t kOrdInf = 0xFF800000u;  // ord_of(+infinity)
 
 // ------------------------------------------------------------------ keys
 __device__ __forceinline__ uint32_t ord_of(float d) {
@@ -476,8 +477,7 @@ __device__ __forceinline__ void write_result(const uint64_t* keys, int c, int k,
 constexpr int kWaveK = 128;
 constexpr int kWaveCap = 256;
 constexpr int kUnitTiles = 8;  // wave-tiles per unit of rows taken by a wave of k_scan_w
-constexpr uint32_t kSeedReady = 1u << 20;    // added to a query's counter once its seeded bound is in tau_g
-constexpr long long kSeedWaitTicks = 5000;   // longest wait for that, in ticks of the 100 MHz clock (50 us)
+constexpr long long kSeedWaitTicks = 5000;   // longest wait for the seeded bound, in ticks of the 100 MHz clock (50 us)
 
 // Cross-block hand-over without cache-wide fences: the data is written with agent-scope
 // atomic stores (which go through to the coherence point), the writer waits for its own stores
@@ -895,9 +895,9 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
         // tile of each of its waves and records the smallest distance among those rows; the
         // k-th smallest of the blocks' minima belongs to k different rows, so it bounds the k-th
         // smallest distance of the whole scan from above.  The block that arrives last selects
-        // it, stores it in tau_g and raises the query's counter by kSeedReady; the others wait
-        // for that -- for at most kSeedWaitTicks of the 100 MHz clock, after which they go on
-        // with whatever bound there is (the bound only saves work, results do not depend on it).
+        // it and stores it in tau_g; the others wait for tau_g to change -- for at most
+        // kSeedWaitTicks of the 100 MHz clock, after which they go on without a bound (the
+        // bound only saves work, results do not depend on it).
         uint32_t best = kOrdMax;
         if (b0 >= 0) {
 #pragma unroll
@@ -921,7 +921,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
           for (int i = 1; i < nwaves; ++i) best = s_min[i] < best ? s_min[i] : best;
           __hip_atomic_store(a.minima + q * gridDim.x + blockIdx.x, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           wait_own_memory_ops();
-          s_last = (atomicAdd(a.counter + q, 1u) & (kSeedReady - 1u)) == gridDim.x - 1;
+          s_last = atomicAdd(a.counter + q, 1u) == gridDim.x - 1;
         }
         __syncthreads();
         if (s_last && wave == 0) {
@@ -943,21 +943,21 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
             for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
             if (c < k) ans = trial;
           }
-          if (lane == 0) {
-            if (ans != kOrdMax) atomicMin(a.tau_g + q, ans);
-            wait_own_memory_ops();
-            atomicAdd(a.counter + q, kSeedReady);
-          }
+          // (fewer than k rows in all first tiles: the image of +infinity still says "seeded"
+          // and lets every row through)
+          if (lane == 0) atomicMin(a.tau_g + q, ans < kOrdInf ? ans : kOrdInf);
         }
         if (tid == 0) {
+          // tau_g leaves kOrdMax exactly once before any wave enters its loop: by that atomicMin
           const long long t0 = wall_clock64();
-          while (__hip_atomic_load(a.counter + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < kSeedReady &&
+          uint32_t seen;
+          while ((seen = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == kOrdMax &&
                  wall_clock64() - t0 < kSeedWaitTicks)
-            __builtin_amdgcn_s_sleep(16);
+            __builtin_amdgcn_s_sleep(4);
+          __hip_atomic_store(&s_tg, seen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         __syncthreads();
-        tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        tg = __hip_atomic_load(&s_tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
       while (b0 >= 0) {  // wave-uniform
         uint64_t key[kRowsPerLane];

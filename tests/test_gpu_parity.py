@@ -122,6 +122,15 @@ def test_linear_scan_one_to_three_queries(M, rii, oracle_lib):
             for i in range(Q):
                 ref = oracle_lib.linear_scan(A[i], codes, topk)
                 assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), (Q, topk, i)
+    # target lists much shorter than the stated upper bound: most blocks of the launch have no
+    # rows, fewer than topk of them can contribute to the seeded bound
+    tids, toff = synth.subset_batch(83, N, [5000, 3])
+    sub = rii.rii_adc_scan_subset(index, lut[:2].contiguous(), tids.cuda(), toff.cuda(), N, 10)
+    torch.cuda.synchronize()
+    tids, toff = t2n(tids), t2n(toff)
+    for i in range(2):
+        ref = oracle_lib.linear_scan(A[i], codes, 10, S=tids[toff[i]:toff[i + 1]])
+        assert np.array_equal(t2n(sub[0])[i], ref[0]) and np.array_equal(t2n(sub[1])[i], ref[1])
 
 
 def test_linear_scan_ties_and_padding(rii, oracle_lib):
