@@ -828,10 +828,12 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
   if constexpr (rot_m(MT)) {
     // Rotated stored form.  Every block has its share of the rows (a.chunk_rows of them), cut
     // into units of kUnitTiles wave-tiles (a wave-tile = 64 lanes x kRowsPerLane consecutive
-    // 64-row slices); the block's waves take the units in turn, so each wave streams runs of
-    // kUnitTiles * 256 consecutive rows and no wave waits for another inside the loop.
-    // (Handing the units out through counters, so that fast blocks take work from slow ones,
-    // was measured slower: the wait for a counter's value drains the wave's load pipeline.)
+    // 64-row slices); the block's waves take the units one after the other from a counter in
+    // LDS, so each wave streams runs of kUnitTiles * 256 consecutive rows, no wave waits for
+    // another inside the loop, and the waves of a block finish together.
+    // (Handing units out across blocks through counters in global memory, so that fast blocks
+    // take work from slow ones, was measured slower: the wait for a counter's value drains the
+    // wave's load pipeline.)
     if (nrows > 0) {  // block-uniform
       // The query's shared bound is re-read once per tile by the block's first wave only and
       // passed on through LDS (a plain word, read without synchronisation: a stale value is
@@ -839,7 +841,10 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
       // Its first value is in place before the barriers of the table fill, hence before any
       // wave can read it.
       uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (tid == 0) __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (tid == 0) {
+        __hip_atomic_store(&s_tg, tg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        bv->cnt = nwaves;  // units of the share handed out so far (the first one per wave is fixed)
+      }
       fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), lut);  // the wave buffers are not in use yet
       constexpr int64_t kWaveTile = 64 * kRowsPerLane;
       constexpr int64_t kUnitRows = kUnitTiles * kWaveTile;
@@ -847,12 +852,21 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w(ScanArgs a) {
       const int64_t share_lo = (int64_t)blockIdx.x * a.chunk_rows;
       const int64_t share_n = share_lo >= nrows ? 0 : (nrows - share_lo < a.chunk_rows ? nrows - share_lo : a.chunk_rows);
       const uint32_t share_units = (uint32_t)((share_n + kUnitRows - 1) / kUnitRows);
-      uint32_t my_next = (uint32_t)wave;
-      // first row of the next unit for this wave, -1 when its part of the share is used up (wave-uniform)
+      // First row of the next unit for this wave, -1 when the share is used up (wave-uniform).
+      // A wave starts with unit number `wave`; further units come from a counter in LDS, so a
+      // wave that runs slower than its neighbours simply takes fewer of them (an LDS atomic
+      // returns through the LDS queue and leaves the wave's global loads in flight).
+      bool first_unit = true;
       auto next_unit = [&]() -> int64_t {
-        if (my_next >= share_units) return -1;
-        const uint32_t u = my_next;
-        my_next += (uint32_t)nwaves;
+        uint32_t u;
+        if (first_unit) {
+          first_unit = false;
+          u = (uint32_t)wave;
+        } else {
+          u = lane == 0 ? (uint32_t)atomicAdd(&bv->cnt, 1) : 0u;
+          u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
+        }
+        if (u >= share_units) return -1;
         return share_lo + (int64_t)u * kUnitRows;
       };
       int64_t unit_base = next_unit();
