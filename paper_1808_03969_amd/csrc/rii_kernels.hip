@@ -1291,6 +1291,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
   // tables: one query at a time through a staging copy (the buffer area), quantised and written
   // along diagonals (see fill_table_rot)
   constexpr uint32_t kCap = 32767u / MT;
+  if (tid == 0) bv->cnt = nwaves;  // units handed out so far (the first one per wave is fixed); before the barriers below
   {
     float* stage = reinterpret_cast<float*>(wbuf);
     uint16_t* T4q = reinterpret_cast<uint16_t*>(smem);
@@ -1369,16 +1370,47 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
         wave_offer<1>(wbuf + j * qstride + (size_t)wave * kWaveCap4, cnt[j], tau[j], k, key, pend, lane, kWaveCap4);
     }
   };
-  const int64_t tile_step = (int64_t)blockDim.x * kRowsPerLane;
-  // row of slot r in the tile at `tile`; past the end: the last row (valid memory, masked later)
-  auto row_at = [&](int64_t tile, int r) -> int64_t {
-    int64_t i = tile + (int64_t)r * blockDim.x + tid;
+  // The block's rows [r0, nrows) in units of kUnitTiles wave-tiles (a wave-tile = kRowsPerLane
+  // slices of 64 consecutive rows), taken by the waves from a counter in LDS as in k_scan_w, so
+  // that the waves of a block finish together.  Units and slices start at multiples of 64, so
+  // lane l always scores rows with row % 32 == l % 32 (what lb4 assumes).
+  constexpr int64_t kWaveTile = 64 * kRowsPerLane;
+  constexpr int64_t kUnitRows = kUnitTiles * kWaveTile;
+  const uint32_t share_units = (uint32_t)((nrows - r0 + kUnitRows - 1) / kUnitRows);
+  bool first_unit = true;
+  auto next_unit = [&]() -> int64_t {
+    uint32_t u;
+    if (first_unit) {
+      first_unit = false;
+      u = (uint32_t)wave;
+    } else {
+      u = lane == 0 ? (uint32_t)atomicAdd(&bv->cnt, 1) : 0u;
+      u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
+    }
+    return u < share_units ? r0 + (int64_t)u * kUnitRows : -1;
+  };
+  int64_t unit_base = next_unit();
+  int t_in = 0;
+  // first row of the wave's next tile, -1 when the rows are used up
+  auto next_tile = [&]() -> int64_t {
+    if (unit_base < 0) return -1;
+    const int64_t base = unit_base + (int64_t)t_in * kWaveTile;
+    if (++t_in == kUnitTiles) {
+      t_in = 0;
+      unit_base = next_unit();
+    }
+    return base < nrows ? base : -1;
+  };
+  // row of slice r of the tile at `base`; past the end (or no tile): the last row (valid memory, masked later)
+  auto row_at = [&](int64_t base, int r) -> int64_t {
+    const int64_t i = base < 0 ? nrows - 1 : base + r * 64 + lane;
     return i < nrows ? i : nrows - 1;
   };
+  int64_t tile = next_tile(), tile_next = next_tile();
   uint32_t w[kRowsPerLane][MT / 4];
 #pragma unroll
-  for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(r0, r) * MT, w[r]);
-  for (int64_t tile = r0; tile < nrows; tile += tile_step) {
+  for (int r = 0; r < kRowsPerLane; ++r) load_row_words<MT>(a.codes + row_at(tile, r) * MT, w[r]);
+  for (; tile >= 0; tile = tile_next, tile_next = next_tile()) {  // wave-uniform
     // C: field j = 0x8000 + fbq_j, fbq_j the filter bound of query j in its table's units
     uint64_t C = 0;
     const float scl[4] = {scale0, scale1, scale2, scale3};
@@ -1400,8 +1432,8 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
     uint32_t plo[kRowsPerLane], phi[kRowsPerLane];
 #pragma unroll
     for (int r = 0; r < kRowsPerLane; ++r) {
-      if (tile + (int64_t)r * blockDim.x + tid < nrows) live |= 1u << r;
-      const uint8_t* next_row = a.codes + row_at(tile + tile_step, r) * MT;
+      if (tile + r * 64 + lane < nrows) live |= 1u << r;
+      const uint8_t* next_row = a.codes + row_at(tile_next, r) * MT;
       uint64_t acc = 0;
 #pragma unroll
       for (int sg = 0; sg < MT / kRotSeg<MT>; ++sg) {
@@ -1450,7 +1482,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_w4(ScanArgs a) {
           const unsigned long long m = __ballot(hit);
           if (m == 0ull) continue;
           if (hit) {
-            const int64_t i = tile + (int64_t)r * blockDim.x + tid;
+            const int64_t i = tile + r * 64 + lane;
             rq[qn + __popcll(m & ((1ull << lane) - 1ull))] = ((uint64_t)j << 32) | (uint32_t)i;
           }
           qn += __popcll(m);
