@@ -1760,8 +1760,9 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf(IvfArgs a) {
 // member of the probed lists is a candidate), or a cap without a target set (the candidates are
 // then simply the first L members in traversal order).  The members are numbered 0 .. total-1
 // in traversal order ("virtual" positions; a prefix sum over the list lengths, kept in LDS, maps
-// them to positions in the list-ordered arrays), cut into units of kUnitTiles wave-tiles and dealt
-// to the waves of the query's blocks in turn -- tiles are full whatever the list lengths are.
+// them to positions in the list-ordered arrays), cut into units of kUnitTiles wave-tiles; the
+// units are dealt to the query's blocks in turn and taken by a block's waves from a counter in
+// LDS -- tiles are full whatever the list lengths are.
 // Scoring, software pipeline and selection as in k_scan_w; identifiers are read for every
 // member only when a target set has to be tested, otherwise only for the few rows that pass the
 // distance filter.
@@ -1799,7 +1800,10 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
     s_start[i] = (uint32_t)b;
     s_pref[i + 1] = (uint32_t)(e - b);
   }
-  if (tid == 0) s_pref[0] = 0u;
+  if (tid == 0) {
+    s_pref[0] = 0u;
+    bv->cnt = nwaves;  // units of this block handed out so far
+  }
   __syncthreads();
   if (wave == 0) {
     const int per = (np + 63) / 64;
@@ -1824,7 +1828,7 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
   constexpr int64_t kWaveTile = 64 * kRowsPerLane;
   constexpr int64_t kUnitRows = kUnitTiles * kWaveTile;
   const int64_t nunits = (total + kUnitRows - 1) / kUnitRows;
-  if ((int64_t)blockIdx.x * nwaves < nunits) {  // block-uniform: at least one wave of this block has a unit
+  if ((int64_t)blockIdx.x < nunits) {  // block-uniform: this block has at least one unit
     const float* lut = a.lut + q * M * 256;
     if constexpr (rot_m(MT)) {
       fill_table_rot<MT>(A, reinterpret_cast<float*>(wbuf), lut);  // the wave buffers are not in use yet
@@ -1844,8 +1848,9 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
     uint32_t tau = kOrdMax;
     uint32_t tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-    int64_t unit = (int64_t)blockIdx.x * nwaves + wave;
-    const int64_t unit_step = (int64_t)gridDim.x * nwaves;
+    // Block b owns the units b, b + gridDim.x, b + 2 gridDim.x, ...; its waves take them one
+    // after the other from a counter in LDS (the first one per wave is fixed).
+    int64_t unit = (int64_t)blockIdx.x + (int64_t)gridDim.x * wave;
     int t_in = 0;
     int hint = 0;  // a list at or before the one the next tile starts in (wave-uniform)
     // One tile of the wave: virtual base (or -1), positions of its kRowsPerLane slices in the
@@ -1882,7 +1887,9 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
       hint = __shfl(p, 63, 64);  // the last member's list: not after the next tile's first
       if (++t_in == kUnitTiles) {
         t_in = 0;
-        unit += unit_step;
+        int c = lane == 0 ? atomicAdd(&bv->cnt, 1) : 0;
+        c = __builtin_amdgcn_readfirstlane(c);
+        unit = (int64_t)blockIdx.x + (int64_t)gridDim.x * c;
       }
       return t;
     };
