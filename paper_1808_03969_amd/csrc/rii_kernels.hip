@@ -1968,6 +1968,10 @@ __global__ __launch_bounds__(kScanThreads) void k_ivf_w(IvfArgs a) {
     tg = __hip_atomic_load(a.tau_g + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint64_t* best;
     const int c = block_collect(wbuf, nwaves, cnt, tau, tg < tau ? tg : tau, k, &best, &s_total, &s_off);
+    if (gridDim.x == 1) {  // the query's only block: its result is the query's result
+      write_result(best, c, k, a.ids + q * a.k, a.dist ? a.dist + q * a.k : nullptr);
+      return;
+    }
     publish_block_result(best, c, k, cand, a.cand_cnt + q, a.tau_g + q, &s_off);
   }
   finish_query(wbuf, nwaves, k, cand, a.cand_cnt + q, a.done_cnt + q, gridDim.x, a.ids + q * a.k,
