@@ -39,10 +39,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # size).  Reported only for the exact configuration they were measured on.
 MEASURED_TRAFFIC = {
     ("c5_billion_shard", 100_000_000, 10_000): {
-        # k_tau0 + k_scan_w, one query: (16,577 + 1,563,614) KiB fetched x 2, (136 + 98) KiB written
-        "single": (16_577 + 1_563_614) * 2.0 * 1024 + (136 + 98) * 1024,
-        # k_scan_w4, 10,000 queries: 2,817,086,371 KiB fetched x 2, 8,127 KiB written
-        "batched": 2_817_086_371 * 2.0 * 1024 + 8_127 * 1024,
+        # k_scan_w, one query: 1,563,866 KiB fetched x 2, 122 KiB written
+        "single": 1_563_866 * 2.0 * 1024 + 122 * 1024,
+        # k_scan_w4, 10,000 queries: 2,417,752,877 KiB fetched x 2, 28,221 KiB written
+        "batched": 2_417_752_877 * 2.0 * 1024 + 28_221 * 1024,
     },
 }
 
