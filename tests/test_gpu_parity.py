@@ -133,6 +133,50 @@ def test_linear_scan_one_to_three_queries(M, rii, oracle_lib):
         assert np.array_equal(t2n(sub[0])[i], ref[0]) and np.array_equal(t2n(sub[1])[i], ref[1])
 
 
+def test_scans_over_random_shapes(rii, oracle_lib):
+    """Forty seeded shape draws (rows, M, batch size, topk, whole database or target lists): every
+    dispatch path of the scan entry points is hit somewhere, each result is compared with the
+    oracle element by element, and every call is made twice (the second must repeat the first)."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        M = int(rng.choice([8, 16, 32, 32, 12, 64]))
+        N = int(rng.choice([1, 63, 4097, 20000, 70001, 140000]))
+        N = max(1, N + int(rng.integers(-40, 40)))
+        Q = int(rng.choice([1, 2, 3, 4, 5, 17, 64, 130, 270]))
+        topk = int(rng.choice([1, 7, 100, 101, 128, 129, 300]))
+        Ds = 2
+        cb = rng.normal(size=(M, 256, Ds)).astype(np.float32)
+        codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+        if N > 300:
+            codes[N // 2:N // 2 + 150] = codes[0]  # a run of exact ties
+        q = rng.normal(size=(Q, M * Ds)).astype(np.float32)
+        index = rii.Index(cb)
+        index.add(codes)
+        lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+        A = oracle_lib.lut(cb, q)
+        subset = bool(rng.integers(0, 2))
+        if subset:
+            sizes = [int(rng.integers(0, N + 1)) for _ in range(Q)]
+            tids, toff = synth.subset_batch(300 + case, N, sizes)
+            args = (index, lut, tids.cuda(), toff.cuda(), max(sizes), topk)
+            call = rii.rii_adc_scan_subset
+            tids, toff = t2n(tids), t2n(toff)
+        else:
+            args = (index, lut, topk)
+            call = rii.rii_adc_scan_linear
+        first = call(*args)
+        torch.cuda.synchronize()
+        again = call(*args)
+        torch.cuda.synchronize()
+        assert torch.equal(first[0], again[0]) and torch.equal(first[1], again[1]), f"case {case}: not repeatable"
+        ids, dist = t2n(first[0]), t2n(first[1])
+        for i in range(0, Q, max(1, Q // 12)):
+            S = tids[toff[i]:toff[i + 1]] if subset else None
+            ref = oracle_lib.linear_scan(A[i], codes, topk, S=S)
+            assert np.array_equal(ids[i], ref[0]) and np.array_equal(dist[i], ref[1]), \
+                f"case {case}: N={N} M={M} Q={Q} topk={topk} subset={subset} query {i}"
+
+
 def test_linear_scan_ties_and_padding(rii, oracle_lib):
     """Many identical codes (exact distance ties) and fewer rows than topk."""
     rng = np.random.default_rng(5)
@@ -306,6 +350,48 @@ def test_ivf_scan_short_and_empty_lists(M, rii, oracle_lib):
                 ref = oracle_lib.inverted_index(d["lut_ref"][i], d["codes"], d["coarse"], d["off"], d["lids"],
                                                 R=20, P=P, S=S, Lcap=L)
                 check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
+def test_ivf_and_query_over_random_shapes(rii, oracle_lib):
+    """Sixteen seeded draws of (rows, M, lists, batch size, lists probed, cap, target lists, topk)
+    for the inverted-index scan and the query procedure, each compared with the oracle."""
+    rng = np.random.default_rng(4242)
+    for case in range(16):
+        M = int(rng.choice([8, 16, 32, 12]))
+        N = int(rng.choice([700, 5000, 20011]))
+        K = int(rng.choice([1, 9, 64, 257]))
+        K = min(K, N)
+        Q = int(rng.choice([1, 3, 8, 40]))
+        topk = int(rng.choice([1, 10, 100, 130]))
+        d = make_index(rii, oracle_lib, N=N, D=2 * M, M=M, K=K, seed=50 + case, iters=2, Q=Q)
+        lut = lut_dev(rii, d)
+        P = int(rng.integers(1, K + 1))
+        L = int(rng.choice([0, 1, 50, N]))
+        use_S = bool(rng.integers(0, 2))
+        sizes = [int(rng.integers(0, N + 1)) for _ in range(Q)]
+        tids, toff = synth.subset_batch(900 + case, N, sizes)
+        tids_d, toff_d = tids.cuda(), toff.cuda()
+        tids, toff = t2n(tids), t2n(toff)
+        probe, _ = rii.rii_coarse_assign(d["index"], lut, P)
+        ids, dist = rii.rii_adc_scan_ivf(d["index"], lut, probe, topk, target_ids=tids_d if use_S else None,
+                                         target_offsets=toff_d if use_S else None, L=L)
+        torch.cuda.synchronize()
+        for i in range(Q):
+            S = tids[toff[i]:toff[i + 1]] if use_S else None
+            ref = oracle_lib.inverted_index(d["lut_ref"][i], d["codes"], d["coarse"], d["off"], d["lids"],
+                                            R=topk, P=P, S=S, Lcap=L)
+            check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+        theta = int(rng.choice([0, N // 3, N + 1]))
+        Lq = max(1, L)
+        d["index"].set_threshold(theta)
+        ids, dist = rii.rii_query(d["index"], d["q_dev"], topk, tids_d if use_S else None, toff_d if use_S else None,
+                                  max(sizes) if use_S else 0, Lq)
+        torch.cuda.synchronize()
+        for i in range(Q):
+            S = tids[toff[i]:toff[i + 1]] if use_S else None
+            ref = oracle_lib.query(d["cb"], d["q"][i], d["codes"], d["coarse"], d["off"], d["lids"], topk, Lq, theta, S=S)
+            check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+        d["index"].set_threshold(0)
 
 
 # ---------------------------------------------------------------- PartialSort + Take
