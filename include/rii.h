@@ -136,6 +136,12 @@ int rii_index_calibrate_threshold(rii_index_t* index, int64_t L, int topk, int n
  * on the call's stream.  Pass NULL, NULL to switch it off.  The caller owns the events. */
 int rii_index_set_scan_events(rii_index_t* index, void* start_event, void* stop_event);
 
+/* Measurement aid: while the scan events are set, the batched linear-scan kernel counts the
+ * slices (64 rows x one group of four queries, i.e. 64 x M table look-ups) it scored and how many
+ * of them it abandoned half-way (then only M/2 look-ups each were made).  Returns the two
+ * counts accumulated since the last call and resets them.  Synchronous (waits for the device). */
+int rii_index_read_scan_counters(rii_index_t* index, uint64_t* slices_scored, uint64_t* slices_abandoned);
+
 /* info_out[0..7] = N, D, M, Ks, K (0 without lists), theta, bytes of the paper's data
  * structure ((N+K) M + 4 N, Sec. 4.1), device bytes actually held by the handle. */
 int rii_index_info(const rii_index_t* index, int64_t* info_out);

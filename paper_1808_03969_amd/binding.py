@@ -310,6 +310,14 @@ def rii_assign(index: Index, codes: torch.Tensor, coarse: torch.Tensor) -> torch
     return out
 
 
+def rii_index_read_scan_counters(index: Index):
+    """(slices scored, slices abandoned half-way) by the batched scan since the last call; resets them."""
+    a, b = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    _check(load_library().rii_index_read_scan_counters(index.handle, ctypes.byref(a), ctypes.byref(b)),
+           "rii_index_read_scan_counters")
+    return a.value, b.value
+
+
 def rii_scan_linear_plan(index: Index, Q: int, topk: int):
     """(queries per block, row chunks per query group) of the launch rii_adc_scan_linear would make."""
     qpb, chunks = ctypes.c_int(0), ctypes.c_int64(0)

@@ -277,6 +277,7 @@ void rii_index_destroy(rii_index_t* idx) {
   free_dev(idx->d_sym);
   free_dev(idx->d_codes);
   if (idx->ws) (void)hipFree(idx->ws);
+  if (idx->d_scan_counters) (void)hipFree(idx->d_scan_counters);
   delete idx;
 }
 
@@ -288,8 +289,24 @@ int rii_index_set_threshold(rii_index_t* idx, int64_t theta) {
 
 int rii_index_set_scan_events(rii_index_t* idx, void* start_event, void* stop_event) {
   if (!idx || ((start_event == nullptr) != (stop_event == nullptr))) return RII_ERR_INVALID_ARG;
+  if (start_event && !idx->d_scan_counters) {
+    RII_HIP(hipMalloc(&idx->d_scan_counters, 2 * sizeof(unsigned long long)));
+    RII_HIP(hipMemset(idx->d_scan_counters, 0, 2 * sizeof(unsigned long long)));
+  }
   idx->ev_start = start_event;
   idx->ev_stop = stop_event;
+  return RII_OK;
+}
+
+int rii_index_read_scan_counters(rii_index_t* idx, uint64_t* slices_scored, uint64_t* slices_abandoned) {
+  if (!idx || !slices_scored || !slices_abandoned) return RII_ERR_INVALID_ARG;
+  *slices_scored = *slices_abandoned = 0;
+  if (!idx->d_scan_counters) return RII_OK;
+  unsigned long long h[2] = {0, 0};
+  RII_HIP(hipMemcpy(h, idx->d_scan_counters, sizeof(h), hipMemcpyDeviceToHost));  // waits for earlier work
+  RII_HIP(hipMemset(idx->d_scan_counters, 0, sizeof(h)));
+  *slices_scored = h[0];
+  *slices_abandoned = h[1];
   return RII_OK;
 }
 

@@ -39,6 +39,9 @@ struct rii_index {
   // optional measurement aid: events recorded right before / after the linear-scan kernel
   void* ev_start = nullptr;
   void* ev_stop = nullptr;
+  // ... and, while the events are set, two device counters the batched scan kernel adds to:
+  // [0] slices (64 rows x one query group) it scored, [1] slices abandoned half-way
+  unsigned long long* d_scan_counters = nullptr;
 };
 
 #define RII_HIP(call)                         \

@@ -176,6 +176,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   dim3 grid((unsigned)nchunks, (unsigned)Q);
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   const bool timed = mode == kLinear && idx->ev_start && idx->ev_stop && codes == idx->d_codes;
+  a.counters = timed ? idx->d_scan_counters : nullptr;
   if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
   if (topk <= kWaveK) {
     // When a query's rows are split over several blocks, a short first pass over the leading
