@@ -42,8 +42,8 @@ MEASURED_TRAFFIC = {
     ("c5_billion_shard", 100_000_000, 10_000): {
         # k_scan_w, one query: 1,563,866 KiB fetched x 2, 122 KiB written
         "single": 1_563_866 * 2.0 * 1024 + 122 * 1024,
-        # k_scan_w4, 10,000 queries: 2,417,752,877 KiB fetched x 2, 28,221 KiB written
-        "batched": 2_417_752_877 * 2.0 * 1024 + 28_221 * 1024,
+        # k_scan_w4, 10,000 queries: 2,676,877,158 KiB fetched x 2, 30,670 KiB written
+        "batched": 2_676_877_158 * 2.0 * 1024 + 30_670 * 1024,
     },
 }
 
