@@ -14,17 +14,22 @@
 #include "rii_internal.h"
 
 extern "C" int rii_internal_sym_table(const rii_index* idx, hipStream_t st);
-extern "C" int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base,
+extern "C" int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base, int64_t plane,
                                    const uint8_t* coarse, int K, int32_t* assign_out, hipStream_t st);
 extern "C" int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base,
+                                          int64_t plane,
                                           const uint8_t* super, int G, const float* radius, const uint8_t* coarse_g,
                                           const int32_t* perm_g, const int32_t* group_off, int32_t* assign_out,
                                           unsigned long long* visited_total, hipStream_t st);
 extern "C" int rii_internal_spread_ids(int32_t* ids, int64_t* offsets, int nq, int64_t S, int64_t N, hipStream_t st);
-extern "C" int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, const int32_t* ids, int64_t n, int M,
-                                      uint8_t* out, int64_t out_rot, hipStream_t st);
+extern "C" int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, int64_t in_plane, const int32_t* ids,
+                                      int64_t n, int M, uint8_t* out, int64_t out_rot, int64_t out_plane,
+                                      hipStream_t st);
 
 namespace {
+
+// byte distance between the two planes of a stored array of `rows` rows (see rii_index)
+int64_t plane_for(int M, int64_t rows) { return M == 32 ? rows * 16 : 0; }
 
 template <typename T>
 void free_dev(T*& p) {
@@ -58,14 +63,17 @@ int install_lists(rii_index* idx, const uint8_t* coarse, int K, const std::vecto
   RII_HIP(hipMalloc(&idx->d_assign, std::max<size_t>((size_t)N * 4, 4)));
   RII_HIP(hipMalloc(&idx->d_codes_list, std::max<size_t>((size_t)N * M, 16)));
   RII_HIP(hipMemcpy(idx->d_coarse, coarse, (size_t)K * M, hipMemcpyHostToDevice));
-  int rc = rii_internal_copy_rows(idx->d_coarse, -1, nullptr, K, M, idx->d_coarse_st, 0, nullptr);
+  idx->plane_coarse = plane_for(M, K);
+  idx->plane_list = plane_for(M, N);
+  int rc = rii_internal_copy_rows(idx->d_coarse, -1, 0, nullptr, K, M, idx->d_coarse_st, 0, idx->plane_coarse, nullptr);
   if (rc) return rc;
   RII_HIP(hipMemcpy(idx->d_list_off, off.data(), (size_t)(K + 1) * 8, hipMemcpyHostToDevice));
   if (N > 0) {
     RII_HIP(hipMemcpy(idx->d_list_ids, ids.data(), (size_t)N * 4, hipMemcpyHostToDevice));
     RII_HIP(hipMemcpy(idx->d_assign, assign.data(), (size_t)N * 4, hipMemcpyHostToDevice));
     // row p of the list-ordered copy = code of identifier list_ids[p], stored form (rotated by p)
-    rc = rii_internal_copy_rows(idx->d_codes, 0, idx->d_list_ids, N, M, idx->d_codes_list, 0, nullptr);
+    rc = rii_internal_copy_rows(idx->d_codes, 0, idx->plane_codes, idx->d_list_ids, N, M, idx->d_codes_list, 0,
+                                idx->plane_list, nullptr);
     if (rc) return rc;
   }
   RII_HIP(hipDeviceSynchronize());
@@ -167,17 +175,17 @@ int make_groups(rii_index* idx, const uint8_t* coarse, int K, CentreGroups& g) {
 }
 
 // a(n) for n device-resident codes `rows` under the host coarse centres `coarse`; the result
-// stays on the device (d_out, n entries).  rot_base >= 0: `rows` are stored rows rot_base.. (stored
-// form), rot_base < 0: plain codes.  Brute force for small K, pruned search
-// (same result) for large K.
-int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, int64_t rot_base, const uint8_t* coarse, int K,
-                    int32_t* d_out) {
+// stays on the device (d_out, n entries).  rot_base >= 0: `rows` is the base of a stored array with
+// planes `plane` apart and the items are its rows rot_base..; rot_base < 0: plain codes.  Brute
+// force for small K, pruned search (same result) for large K.
+int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, int64_t rot_base, int64_t plane,
+                    const uint8_t* coarse, int K, int32_t* d_out) {
   if (n == 0) return RII_OK;
   if (K >= kPruneMinK) {
     CentreGroups g;
     int rc = make_groups(idx, coarse, K, g);
     if (rc) return rc;
-    rc = rii_internal_assign_pruned(idx, rows, n, rot_base, g.d_super, g.G, g.d_radius, g.d_coarse_g, g.d_perm_g,
+    rc = rii_internal_assign_pruned(idx, rows, n, rot_base, plane, g.d_super, g.G, g.d_radius, g.d_coarse_g, g.d_perm_g,
                                     g.d_group_off, d_out, nullptr, nullptr);
     if (rc) return rc;
     RII_HIP(hipDeviceSynchronize());
@@ -187,7 +195,7 @@ int assign_rows_dev(rii_index* idx, const uint8_t* rows, int64_t n, int64_t rot_
   RII_HIP(hipMalloc(&d_coarse, (size_t)K * idx->M));
   int rc = RII_OK;
   if (hipMemcpy(d_coarse, coarse, (size_t)K * idx->M, hipMemcpyHostToDevice) != hipSuccess) rc = RII_ERR_DEVICE;
-  if (!rc) rc = rii_internal_assign(idx, rows, n, rot_base, d_coarse, K, d_out, nullptr);
+  if (!rc) rc = rii_internal_assign(idx, rows, n, rot_base, plane, d_coarse, K, d_out, nullptr);
   if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
   (void)hipFree(d_coarse);
   return rc;
@@ -197,7 +205,7 @@ int assign_stored(rii_index* idx, int64_t first, int64_t n, const uint8_t* coars
   if (n == 0) return RII_OK;
   int32_t* d_out = nullptr;
   RII_HIP(hipMalloc(&d_out, (size_t)n * 4));
-  int rc = assign_rows_dev(idx, idx->d_codes + first * idx->M, n, first, coarse, K, d_out);
+  int rc = assign_rows_dev(idx, idx->d_codes, n, first, idx->plane_codes, coarse, K, d_out);
   if (!rc && hipMemcpy(assign_host, d_out, (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
   (void)hipFree(d_out);
   return rc;
@@ -276,6 +284,7 @@ void rii_index_destroy(rii_index_t* idx) {
   free_dev(idx->d_cb);
   free_dev(idx->d_sym);
   free_dev(idx->d_codes);
+  idx->d_codes_rows = nullptr;  // part of the same allocation
   if (idx->ws) (void)hipFree(idx->ws);
   if (idx->d_scan_counters) (void)hipFree(idx->d_scan_counters);
   delete idx;
@@ -398,7 +407,7 @@ int rii_index_info(const rii_index_t* idx, int64_t* info) {
   const int64_t N = idx->N, M = idx->M, K = idx->K;
   info[0] = N; info[1] = idx->D; info[2] = M; info[3] = idx->Ks; info[4] = K; info[5] = idx->theta;
   info[6] = (N + K) * M + 4 * N;
-  int64_t dev = (int64_t)M * 256 * idx->Ds * 4 + idx->cap * M + (int64_t)idx->ws_bytes;
+  int64_t dev = (int64_t)M * 256 * idx->Ds * 4 + idx->cap * M * (idx->plane_codes ? 2 : 1) + (int64_t)idx->ws_bytes;
   if (idx->d_sym) dev += M * 256 * 256 * 4;
   if (K > 0) dev += K * M + (K + 1) * 8 + N * 4 /*ids*/ + N * 4 /*assign*/ + N * M /*list-ordered codes*/;
   info[7] = dev;
@@ -414,15 +423,28 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
   if (idx->N + n > idx->cap) {
     int64_t ncap = std::max<int64_t>(idx->N + n, idx->cap + idx->cap / 2);
     uint8_t* nb = nullptr;
-    if (hipMalloc(&nb, (size_t)ncap * M) != hipSuccess) {
+    // (M = 32 keeps the codes twice, as two planes and as whole rows: one allocation, rows last)
+    const size_t copies = plane_for(M, 1) ? 2 : 1;
+    if (hipMalloc(&nb, copies * (size_t)ncap * M) != hipSuccess) {
       (void)hipGetLastError();
       ncap = idx->N + n;
-      RII_HIP(hipMalloc(&nb, (size_t)ncap * M));
+      RII_HIP(hipMalloc(&nb, copies * (size_t)ncap * M));
     }
-    if (idx->N > 0) RII_HIP(hipMemcpy(nb, idx->d_codes, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
+    const int64_t nplane = plane_for(M, ncap);
+    if (idx->N > 0) {
+      if (nplane) {  // each plane holds 16 bytes a row
+        RII_HIP(hipMemcpy(nb, idx->d_codes, (size_t)idx->N * 16, hipMemcpyDeviceToDevice));
+        RII_HIP(hipMemcpy(nb + nplane, idx->d_codes + idx->plane_codes, (size_t)idx->N * 16, hipMemcpyDeviceToDevice));
+        RII_HIP(hipMemcpy(nb + (size_t)ncap * M, idx->d_codes_rows, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
+      } else {
+        RII_HIP(hipMemcpy(nb, idx->d_codes, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
+      }
+    }
     free_dev(idx->d_codes);
     idx->d_codes = nb;
     idx->cap = ncap;
+    idx->plane_codes = nplane;
+    idx->d_codes_rows = nplane ? nb + (size_t)ncap * M : nb;
   }
   {
     // bring the new rows into stored form (row r rotated by r bytes when M is 8, 16 or 32)
@@ -437,7 +459,9 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
       }
       src = stage;
     }
-    int rc = rii_internal_copy_rows(src, -1, nullptr, n, M, idx->d_codes + idx->N * M, idx->N, nullptr);
+    int rc = rii_internal_copy_rows(src, -1, 0, nullptr, n, M, idx->d_codes, idx->N, idx->plane_codes, nullptr);
+    if (!rc && idx->d_codes_rows != idx->d_codes)
+      rc = rii_internal_copy_rows(src, -1, 0, nullptr, n, M, idx->d_codes_rows, idx->N, 0, nullptr);
     if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
     if (stage) (void)hipFree(stage);
     if (rc) return rc;
@@ -517,7 +541,7 @@ int rii_index_reconfigure(rii_index_t* idx, int K, int iters, uint64_t seed) {
     RII_HIP(hipMalloc(&d_rows, (size_t)ns * 4));
     RII_HIP(hipMalloc(&d_tmp, (size_t)ns * M));
     RII_HIP(hipMemcpy(d_rows, r32.data(), (size_t)ns * 4, hipMemcpyHostToDevice));
-    int rc = rii_internal_copy_rows(idx->d_codes, 0, d_rows, ns, M, d_tmp, -1, nullptr);
+    int rc = rii_internal_copy_rows(idx->d_codes, 0, idx->plane_codes, d_rows, ns, M, d_tmp, -1, 0, nullptr);
     if (rc) return rc;
     RII_HIP(hipMemcpy(sample.data(), d_tmp, sample.size(), hipMemcpyDeviceToHost));
     (void)hipFree(d_rows);
@@ -558,7 +582,7 @@ int rii_index_reconfigure(rii_index_t* idx, int K, int iters, uint64_t seed) {
     RII_HIP(hipMemcpy(d_sample, sample.data(), sample.size(), hipMemcpyHostToDevice));
     std::vector<int32_t> assign(ns);
     for (int it = 0; it < iters; ++it) {
-      int rc2 = assign_rows_dev(idx, d_sample, ns, -1, coarse.data(), K, d_assign);
+      int rc2 = assign_rows_dev(idx, d_sample, ns, -1, 0, coarse.data(), K, d_assign);
       if (rc2) return rc2;
       RII_HIP(hipMemcpy(assign.data(), d_assign, (size_t)ns * 4, hipMemcpyDeviceToHost));
       rii_host::update_centres(sample.data(), ns, assign.data(), sym.data(), M, K, coarse.data());
@@ -593,7 +617,7 @@ int rii_index_get_codes(const rii_index_t* idx, int64_t first, int64_t n, uint8_
     RII_HIP(hipMalloc(&stage, (size_t)n * M));
     dst = stage;
   }
-  int rc = rii_internal_copy_rows(idx->d_codes + first * M, first, nullptr, n, M, dst, -1, nullptr);  // plain form
+  int rc = rii_internal_copy_rows(idx->d_codes, first, idx->plane_codes, nullptr, n, M, dst, -1, 0, nullptr);  // plain form
   if (!rc && hipDeviceSynchronize() != hipSuccess) rc = RII_ERR_DEVICE;
   if (!rc && stage && hipMemcpy(codes_out, stage, (size_t)n * M, hipMemcpyDeviceToHost) != hipSuccess) rc = RII_ERR_DEVICE;
   if (stage) (void)hipFree(stage);

@@ -21,7 +21,15 @@ struct rii_index {
   float* d_sym = nullptr;         // [M][256][256] code-word-to-code-word squared distances (lazy)
   // "Stored" code arrays (d_codes, d_codes_list, d_coarse_st) keep row r rotated by r bytes when
   // M is 8, 16 or 32 (stored[r][t] = code[r][(t + r) % M]), plain otherwise; see rii_kernels.hip.
+  // For M = 32 a stored array is two planes: bytes 0..15 of every row first (16 bytes a row), then,
+  // plane_* bytes further, bytes 16..31 of every row; plane_* is 0 for every other M.  A scan that
+  // settles most rows after 16 look-ups then leaves the second plane alone.  Gathered rows (a
+  // target set) want whole rows instead, one cache line a row: for M = 32 the codes are kept a
+  // second time in that form (d_codes_rows, the tail of d_codes' allocation); for every other M
+  // d_codes_rows is d_codes.
+  int64_t plane_codes = 0, plane_list = 0, plane_coarse = 0;
   uint8_t* d_codes = nullptr;     // [cap][M] codes in identifier order (the linear array), stored form
+  uint8_t* d_codes_rows = nullptr;  // [cap][M] the same rows, rotated, never split (what the subset scan gathers from)
   uint8_t* d_coarse = nullptr;    // [K][M] coarse centres (PQ codes), plain
   uint8_t* d_coarse_st = nullptr; // [K][M] coarse centres, stored form (what the coarse ranking scans)
   int64_t* d_list_off = nullptr;  // [K+1]

@@ -140,7 +140,7 @@ bool plan_batch(int M, int Q, int64_t rows, int topk, int64_t* nchunks_out, int6
 
 // Scan `nrows_max` rows per query (linear: the whole array) and leave per-block partial keys in
 // the workspace; then select.  Workspace layout: [tau Q u32][partial Q*nchunks*k u64].
-int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const float* lut, int Q, int mode,
+int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64_t N, const float* lut, int Q, int mode,
                 const int32_t* target_ids, const int64_t* target_offsets, int64_t max_rows, int topk,
                 int32_t* ids, float* dist, int out_stride, const int* qmode, int want_mode, void* ws_base,
                 hipStream_t st) {
@@ -161,7 +161,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t N, const flo
   uint64_t* partial = reinterpret_cast<uint64_t*>(base + kScanArrays * cstride * 4);
 
   ScanArgs a{};
-  a.codes = codes; a.N = N; a.M = M; a.lut = lut;
+  a.codes = codes; a.plane = plane; a.N = N; a.M = M; a.lut = lut;
   a.target_ids = target_ids; a.target_offsets = target_offsets;
   a.chunk_rows = chunk_rows; a.k = topk; a.partial = partial; a.tau_g = tau;
   int64_t bchunks, brows;
@@ -356,7 +356,7 @@ int rii_adc_scan_linear(const rii_index_t* idx, const float* lut, int Q, int top
   if (idx->N < 1) return RII_ERR_INVALID_ARG;
   int rc = ensure_ws(idx, scan_ws_bytes(idx->M, Q, idx->N, topk));
   if (rc) return rc;
-  return launch_scan(idx, idx->d_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
+  return launch_scan(idx, idx->d_codes, idx->plane_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
                      nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
 }
 
@@ -371,7 +371,7 @@ int rii_adc_scan_subset(const rii_index_t* idx, const float* lut, int Q, const i
   int64_t rows = std::max<int64_t>(max_targets, 1);
   int rc = ensure_ws(idx, scan_ws_bytes(idx->M, Q, rows, topk));
   if (rc) return rc;
-  return launch_scan(idx, idx->d_codes, idx->N, lut, Q, kSubset, target_ids, target_offsets, rows, topk, ids, dist,
+  return launch_scan(idx, idx->d_codes_rows, 0, idx->N, lut, Q, kSubset, target_ids, target_offsets, rows, topk, ids, dist,
                      topk, nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
 }
 
@@ -405,7 +405,7 @@ static int coarse_rank(const rii_index* idx, const float* lut, int Q, int nprobe
                        int out_stride, const int* qmode, int want_mode, void* ws, hipStream_t st) {
   const int M = idx->M, K = idx->K;
   if (nprobe <= RII_MAX_TOPK) {
-    return launch_scan(idx, idx->d_coarse_st, K, lut, Q, kLinear, nullptr, nullptr, K, nprobe, list_ids, list_d0,
+    return launch_scan(idx, idx->d_coarse_st, idx->plane_coarse, K, lut, Q, kLinear, nullptr, nullptr, K, nprobe, list_ids, list_d0,
                        out_stride, qmode, want_mode, ws, st);
   }
   if (K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
@@ -457,7 +457,7 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
                       hipStream_t st) {
   const int M = idx->M;
   IvfArgs a{};
-  a.codes_list = idx->d_codes_list; a.list_ids = idx->d_list_ids; a.list_off = idx->d_list_off; a.M = M;
+  a.codes_list = idx->d_codes_list; a.plane = idx->plane_list; a.list_ids = idx->d_list_ids; a.list_off = idx->d_list_off; a.M = M;
   a.lut = lut; a.probe = probe; a.probe_stride = probe_stride; a.nprobe = nprobe; a.nprobe_q = nprobe_q;
   a.target_ids = target_ids; a.target_offsets = target_offsets; a.Lcap = L; a.k = topk;
   a.ids = ids; a.dist = dist; a.qmode = qmode; a.want_mode = want_mode;
@@ -548,10 +548,10 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
   k_plan<<<(Q + 255) / 256, 256, 0, st>>>(target_offsets, idx->N, Q, idx->theta, K, L, pmax, qmode, nprobe_q);
   // linear-scan branch (mode 0)
   if (target_ids) {
-    rc = launch_scan(idx, idx->d_codes, idx->N, lut, Q, kSubset, target_ids, target_offsets, lin_rows, topk, ids,
+    rc = launch_scan(idx, idx->d_codes_rows, 0, idx->N, lut, Q, kSubset, target_ids, target_offsets, lin_rows, topk, ids,
                      dist, topk, qmode, 0, stage_ws, st);
   } else if (!has_lists || idx->N < idx->theta) {
-    rc = launch_scan(idx, idx->d_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
+    rc = launch_scan(idx, idx->d_codes, idx->plane_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
                      qmode, 0, stage_ws, st);
   }
   if (rc) return rc;
@@ -610,20 +610,20 @@ int rii_internal_sym_table(const rii_index* cidx, hipStream_t st) {
   return RII_OK;
 }
 
-// a(n) by brute force.  rot_base >= 0: `codes` are stored rows rot_base .. rot_base+n-1 (rotated
-// storage when rot_m(M)); rot_base < 0: plain codes.
-int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base, const uint8_t* coarse,
-                        int K, int32_t* assign_out, hipStream_t st) {
+// a(n) by brute force.  rot_base >= 0: `codes` is the base of a stored array (planes `plane`
+// apart) and the items are its rows rot_base .. rot_base+n-1; rot_base < 0: n plain codes.
+int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base, int64_t plane,
+                        const uint8_t* coarse, int K, int32_t* assign_out, hipStream_t st) {
   if (!m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
   if (n == 0) return RII_OK;
-  if (!rot_m(idx->M)) rot_base = -1;
+  if (!rot_m(idx->M) && rot_base >= 0) { codes += rot_base * idx->M; rot_base = -1; }
   int rc = rii_internal_sym_table(idx, st);
   if (rc) return rc;
   const int M = idx->M;
   const size_t lds = (size_t)M * 1024;
   int blocks = (int)std::min<int64_t>(n, 256 * 16);
   DISPATCH_M(M, { int rc2 = set_lds(k_assign<MT>, lds); if (rc2) return rc2;
-                  k_assign<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, M, coarse, K, assign_out); });
+                  k_assign<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, plane, M, coarse, K, assign_out); });
   RII_HIP(hipGetLastError());
   return RII_OK;
 }
@@ -631,17 +631,17 @@ int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, i
 int rii_assign(const rii_index_t* idx, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,
                int32_t* assign_out, void* stream) {
   if (!idx || n < 0 || K < 1 || !coarse || (n > 0 && (!codes || !assign_out))) return RII_ERR_INVALID_ARG;
-  return rii_internal_assign(idx, codes, n, -1, coarse, K, assign_out, static_cast<hipStream_t>(stream));
+  return rii_internal_assign(idx, codes, n, -1, 0, coarse, K, assign_out, static_cast<hipStream_t>(stream));
 }
 
 // a(n) with pruning (see k_assign_pruned); all pointers device.  visited_total may be NULL.
-int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base,
+int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base, int64_t plane,
                                const uint8_t* super, int G,
                                const float* radius, const uint8_t* coarse_g, const int32_t* perm_g,
                                const int32_t* group_off, int32_t* assign_out, unsigned long long* visited_total,
                                hipStream_t st) {
   if (n == 0) return RII_OK;
-  if (!rot_m(idx->M)) rot_base = -1;
+  if (!rot_m(idx->M) && rot_base >= 0) { codes += rot_base * idx->M; rot_base = -1; }
   int rc = rii_internal_sym_table(idx, st);
   if (rc) return rc;
   const int M = idx->M;
@@ -649,7 +649,8 @@ int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64
   if (lds > 150 * 1024) return RII_ERR_UNSUPPORTED;
   int blocks = (int)std::min<int64_t>(n, 256 * 32);
   DISPATCH_M(M, { int rc2 = set_lds(k_assign_pruned<MT>, lds); if (rc2) return rc2;
-                  k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, M, super, G, radius, coarse_g,
+                  k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, plane, M, super, G, radius,
+                                                               coarse_g,
                                                                perm_g, group_off, assign_out, visited_total); });
   RII_HIP(hipGetLastError());
   return RII_OK;
@@ -663,21 +664,27 @@ int rii_internal_spread_ids(int32_t* ids, int64_t* offsets, int nq, int64_t S, i
   return RII_OK;
 }
 
-// used by rii_index.hip: see k_copy_rows.  The rotation arguments are ignored (plain) unless rot_m(M).
-int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, const int32_t* ids, int64_t n, int M, uint8_t* out,
-                           int64_t out_rot, hipStream_t st) {
+// used by rii_index.hip: see k_copy_rows.  For M without a stored form the rotation arguments only
+// select the first row of the (plain) arrays.
+int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, int64_t in_plane, const int32_t* ids, int64_t n, int M,
+                           uint8_t* out, int64_t out_rot, int64_t out_plane, hipStream_t st) {
   if (n == 0) return RII_OK;
-  if (!rot_m(M)) in_rot = out_rot = -1;
+  if (!rot_m(M)) {
+    if (in_rot > 0) in += in_rot * M;
+    if (out_rot > 0) out += out_rot * M;
+    in_rot = out_rot = -1;
+  }
   const int M4 = M / 4;
   const int64_t per = ((int64_t)1 << 30) / M4;  // rows per launch
   for (int64_t r0 = 0; r0 < n; r0 += per) {
     int64_t cnt = std::min<int64_t>(per, n - r0);
     int64_t dw = cnt * M4;
-    // rows r0.. of this call: shift the rotation bases and (when not gathering) the source pointer
-    k_copy_rows<<<(unsigned)((dw + 255) / 256), 256, 0, st>>>(ids ? in : in + r0 * M,
-                                                           in_rot >= 0 && !ids ? in_rot + r0 : in_rot,
-                                                           ids ? ids + r0 : nullptr, cnt, M, out + r0 * M,
-                                                           out_rot >= 0 ? out_rot + r0 : out_rot);
+    // rows r0.. of this call: shift the row bases of stored arrays, the pointers of plain ones
+    const bool seq = !ids;  // source rows follow the output rows
+    k_copy_rows<<<(unsigned)((dw + 255) / 256), 256, 0, st>>>(
+        seq && in_rot < 0 ? in + r0 * M : in, seq && in_rot >= 0 ? in_rot + r0 : in_rot, in_plane,
+        ids ? ids + r0 : nullptr, cnt, M, out_rot < 0 ? out + r0 * M : out, out_rot >= 0 ? out_rot + r0 : out_rot,
+        out_plane);
   }
   RII_HIP(hipGetLastError());
   return RII_OK;
