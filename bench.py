@@ -89,8 +89,8 @@ def main():
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (see DESIGN.md, 'More than one "
-              "GPU'). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (queries and codes would shard "
+              "over GPUs with a top-k merge, which is not built). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
