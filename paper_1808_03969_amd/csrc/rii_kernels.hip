@@ -132,7 +132,7 @@ bool plan_batch(int M, int Q, int64_t rows, int topk, int64_t* nchunks_out, int6
     chunk_rows = (chunk_rows + tile - 1) / tile * tile;
     nchunks = (rows + chunk_rows - 1) / chunk_rows;
   }
-  if (groups * nchunks < kWantBlocks) return false;
+  if (groups * nchunks < kWantBlocks / 4) return false;  // (a quarter of the CUs busy with four queries each still wins)
   *nchunks_out = nchunks;
   *chunk_rows_out = chunk_rows;
   return true;
@@ -182,7 +182,15 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
     // When a query's rows are split over several blocks, a short first pass over the leading
     // rows seeds the shared bound, so that the main pass starts with few candidates.
     const int64_t tile_rows = (int64_t)kScanThreads * kRowsPerLane;
-    const int pre_blocks = (int)std::min<int64_t>(kPrepassBlocks, (max_rows + tile_rows - 1) / tile_rows);
+    const int64_t tiles = (max_rows + tile_rows - 1) / tile_rows;
+    int pre_blocks = (int)std::min<int64_t>(kPrepassBlocks, tiles);
+    if (Q >= 4) {
+      // Many queries: the seeding blocks no longer run side by side, each costs a table fill, and
+      // on a small array 256 of them per query would score all of it once more.  A thirty-second
+      // of the rows is enough for a useful bound, as long as there are at least topk wave minima.
+      const int64_t least = std::min<int64_t>(tiles, (topk + kScanThreads / 64 - 1) / (kScanThreads / 64) + 1);
+      pre_blocks = (int)std::max<int64_t>(least, std::min<int64_t>(pre_blocks, tiles / 32));
+    }
     // The single-query kernel seeds the bound itself when all its blocks run at once and a query
     // has at least topk of them (rotated form only); otherwise a separate pass does it.
     const bool seed_inside = nchunks > 1 && rot_m(M) && !batched && nchunks >= topk && nchunks <= kPrepassBlocks &&
