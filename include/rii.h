@@ -89,6 +89,9 @@ int rii_index_create(const float* codebooks, int D, int M, int Ks, rii_index_t**
  * is also pushed to the list of its nearest coarse centre a(n) (Sec. 4.1), keeping every list
  * in ascending identifier order.
  *   codes [n][M] uint8, in host or device memory as `mem` says (RII_MEM_*).
+ * Device memory held per code: M bytes, 2 M for M = 32 (which keeps the codes in two layouts, one
+ * for sequential and one for gathered scans), plus M + 8 once posting lists are installed
+ * (list-ordered copy, identifier, a(n)); rii_index_info reports the total.
  * Synchronous. */
 int rii_index_add(rii_index_t* index, const uint8_t* codes, int64_t n, int mem);
 
