@@ -41,10 +41,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # size).  Reported only for the exact configuration they were measured on.
 MEASURED_TRAFFIC = {
     ("c5_billion_shard", 100_000_000, 10_000): {
-        # k_scan_w, one query: 797,582 KiB fetched x 2, 135 KiB written
-        "single": 797_582 * 2.0 * 1024 + 135 * 1024,
-        # k_scan_w4, 10,000 queries: 1,712,204,828 KiB fetched x 2, 5,267,638 KiB written
-        "batched": 1_712_204_828 * 2.0 * 1024 + 5_267_638 * 1024,
+        # k_scan_w, one query: 797,609 KiB fetched x 2, 135 KiB written
+        "single": 797_609 * 2.0 * 1024 + 135 * 1024,
+        # k_scan_w4, 10,000 queries: 1,383,577,557 KiB fetched x 2, 10,709 KiB written
+        "batched": 1_383_577_557 * 2.0 * 1024 + 10_709 * 1024,
     },
 }
 
