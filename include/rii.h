@@ -182,10 +182,21 @@ int rii_coarse_assign(const rii_index_t* index, const float* lut, int Q, int npr
 int rii_adc_scan_linear(const rii_index_t* index, const float* lut, int Q, int topk, int32_t* ids,
                         float* dist, void* stream);
 
+/* Optional check of the precondition the two calls below place on target identifiers (Sec. 4.2:
+ * "sorted integers"): inside each query's range strictly increasing and all in [0, N).
+ *   target_ids device int32 (may be NULL when every range is empty); target_offsets device [Q+1]
+ *   int64, non-decreasing from a non-negative start.
+ * Synchronous (waits for the stream).  Returns RII_OK, RII_ERR_UNSORTED_IDS when an identifier
+ * breaks the rule, RII_ERR_INVALID_ARG when the offsets do.  Reads nothing beyond
+ * target_offsets[Q] identifiers when the offsets are valid. */
+int rii_check_target_ids(const rii_index_t* index, const int32_t* target_ids, const int64_t* target_offsets, int Q,
+                         void* stream);
+
 /* Alg. 1 over target identifiers: query i scores only the codes whose identifiers are
  * target_ids[target_offsets[i] .. target_offsets[i+1]).
  *   target_ids device int32, strictly increasing inside each query's range, all in [0, N)
- *   (precondition, Sec. 4.2; not checked); target_offsets device [Q+1] int64;
+ *   (precondition, Sec. 4.2; not checked here, see rii_check_target_ids); target_offsets device
+ *   [Q+1] int64;
  *   max_targets: an upper bound on the largest range length (host value; sizes the launch). */
 int rii_adc_scan_subset(const rii_index_t* index, const float* lut, int Q, const int32_t* target_ids,
                         const int64_t* target_offsets, int64_t max_targets, int topk, int32_t* ids,

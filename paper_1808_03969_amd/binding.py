@@ -233,6 +233,13 @@ def rii_adc_scan_linear(index: Index, lut: torch.Tensor, topk: int, out=None):
     return ids, dist
 
 
+def rii_check_target_ids(index: Index, target_ids: torch.Tensor | None, target_offsets: torch.Tensor) -> int:
+    """Status of the precondition check (0, RII_ERR_UNSORTED_IDS or RII_ERR_INVALID_ARG); does not raise."""
+    Q = target_offsets.numel() - 1
+    tid = _dp(target_ids, torch.int32) if target_ids is not None and target_ids.numel() else None
+    return int(load_library().rii_check_target_ids(index.handle, tid, _dp(target_offsets, torch.int64), Q, _stream()))
+
+
 def rii_adc_scan_subset(index: Index, lut: torch.Tensor, target_ids: torch.Tensor, target_offsets: torch.Tensor,
                         max_targets: int, topk: int, out=None):
     Q = lut.shape[0]

@@ -368,6 +368,24 @@ int rii_adc_scan_linear(const rii_index_t* idx, const float* lut, int Q, int top
                      nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
 }
 
+int rii_check_target_ids(const rii_index_t* idx, const int32_t* target_ids, const int64_t* target_offsets, int Q,
+                         void* stream) {
+  if (!idx || !target_offsets || Q < 1) return RII_ERR_INVALID_ARG;
+  if (Q > 65535) return RII_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = ensure_ws(idx, 256);
+  if (rc) return rc;
+  uint32_t* flag = static_cast<uint32_t*>(idx->ws);
+  RII_HIP(hipMemsetAsync(flag, 0, 4, st));
+  k_check_targets<<<Q, 256, 0, st>>>(target_ids, target_offsets, idx->N, flag);
+  RII_HIP(hipGetLastError());
+  uint32_t h = 0;
+  RII_HIP(hipMemcpyAsync(&h, flag, 4, hipMemcpyDeviceToHost, st));
+  RII_HIP(hipStreamSynchronize(st));
+  if (h & 2u) return RII_ERR_INVALID_ARG;
+  return h ? RII_ERR_UNSORTED_IDS : RII_OK;
+}
+
 int rii_adc_scan_subset(const rii_index_t* idx, const float* lut, int Q, const int32_t* target_ids,
                         const int64_t* target_offsets, int64_t max_targets, int topk, int32_t* ids, float* dist,
                         void* stream) {

@@ -573,6 +573,25 @@ def test_add_in_odd_pieces_and_read_back(rii, oracle_lib):
             assert np.array_equal(t2n(sub[0])[i], ref[0]) and np.array_equal(t2n(sub[1])[i], ref[1])
 
 
+def test_check_target_ids(rii, idx8):
+    """The optional precondition check on target identifiers (sorted, in range; Sec. 4.2)."""
+    index, N = idx8["index"], idx8["N"]
+    dev = lambda a, t: torch.tensor(a, dtype=t).cuda()
+    off = dev([0, 3, 3, 6], torch.int64)
+    assert rii.rii_check_target_ids(index, dev([0, 5, N - 1, 2, 3, 4], torch.int32), off) == 0
+    assert rii.rii_check_target_ids(index, None, dev([0, 0, 0], torch.int64)) == 0
+    # a descent is fine across two queries' ranges, not inside one
+    assert rii.rii_check_target_ids(index, dev([0, 5, 4, 2, 3, 4], torch.int32), off) == -4
+    assert rii.rii_check_target_ids(index, dev([0, 5, 5, 2, 3, 4], torch.int32), off) == -4   # repeated
+    assert rii.rii_check_target_ids(index, dev([0, 5, N, 2, 3, 4], torch.int32), off) == -4   # out of range
+    assert rii.rii_check_target_ids(index, dev([-1, 5, 6, 2, 3, 4], torch.int32), off) == -4
+    assert rii.rii_check_target_ids(index, dev([0, 5, 6, 2, 3, 4], torch.int32), dev([0, 4, 3, 6], torch.int64)) == -1
+    big = torch.arange(0, N, 3, dtype=torch.int32).cuda()
+    assert rii.rii_check_target_ids(index, big, dev([0, big.numel()], torch.int64)) == 0
+    big[big.numel() // 2] = 0
+    assert rii.rii_check_target_ids(index, big, dev([0, big.numel()], torch.int64)) == -4
+
+
 def test_error_codes(rii, idx8):
     """Argument errors come back as status codes and leave the outputs untouched."""
     d = idx8
