@@ -18,7 +18,7 @@ by HBM; with early abandoning over the two-plane layout of M = 32 it moves about
 code byte, so the bound is the LDS look-up rate; `achieved` counts the look-ups the kernel really
 made -- it abandons part of them -- and the ceiling is measured live with the library's
 look-up-only kernel).  `cpu_baseline` is the CPU oracle's linear scan timed single-threaded on a
-bounded sample of the same codes.
+bounded sample of the same codes (and, beside it, on all host threads with one query each).
 """
 from __future__ import annotations
 
@@ -255,6 +255,17 @@ def main():
         cpu = {"value": round(nq * n_s / dt, 1), "unit": "codes/s", "cores": 1, "kind": "oracle",
                "sample": f"Alg. 1 linear scan of the first {n_s} codes for {nq} queries, top-{R}, single thread",
                "ms_per_query_full_scan": round(dt / nq * 1e3 * (N / n_s), 1)}
+        # The same single-threaded oracle function on P host threads, one query each (independent
+        # queries; the call releases the interpreter lock).
+        from concurrent.futures import ThreadPoolExecutor
+        P = max(1, min(Q, int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)))
+        Ap = lut[:P].cpu().numpy()
+        with ThreadPoolExecutor(P) as pool:
+            t0 = time.perf_counter()
+            list(pool.map(lambda i: oracle.linear_scan(Ap[i], codes_h, R), range(P)))
+            dtp = time.perf_counter() - t0
+        cpu["all_threads"] = {"value": round(P * n_s / dtp, 1), "unit": "codes/s", "cores": P,
+                              "sample": f"the same scan for {P} queries, one per thread"}
 
     line = {
         "metric": "ADC codes scanned/sec (% of HBM peak) + queries/sec at top-k=100, 1 MI355X", "value": round(value, 1), "unit": "codes/s", "n_gpus": 1,
