@@ -478,9 +478,11 @@ def test_assign_and_build_lists(rii, oracle_lib, idx16):
     assert inf["paper_bytes"] == oracle_lib.index_bytes(40000, d["K"], d["M"])
 
 
-def test_add_then_search_then_reconfigure(rii, oracle_lib):
-    """Data addition keeps the lists of the old centres (Sec. 4.3); reconfigure rebuilds them."""
-    d = make_index(rii, oracle_lib, N=20000, D=96, M=16, K=20, kind="mixture", seed=11, Q=8)
+@pytest.mark.parametrize("M", [16, 32])
+def test_add_then_search_then_reconfigure(M, rii, oracle_lib):
+    """Data addition keeps the lists of the old centres (Sec. 4.3); reconfigure rebuilds them.
+    (M = 32 keeps its codes in two planes plus a whole-row copy: all three must follow.)"""
+    d = make_index(rii, oracle_lib, N=20000, D=96, M=M, K=20, kind="mixture", seed=11, Q=8)
     extra_x = t2n(synth.mixture(6011, 0, 4000, 96, shift=0.5, means_seed=1011))
     extra = rii.rii_encode(d["cb"], extra_x)
     d["index"].add(extra)
@@ -511,6 +513,18 @@ def test_add_then_search_then_reconfigure(rii, oracle_lib):
     for i in range(8):
         ref = oracle_lib.inverted_index(d["lut_ref"][i], codes, coarse1, off1, lids1, R=50, P=6)
         check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    # the other views of the grown code array: linear scan, gathered scan, read-back
+    lin = rii.rii_adc_scan_linear(d["index"], lut, 50)
+    tids = torch.arange(1, codes.shape[0], 5, dtype=torch.int32).cuda()
+    toff = torch.tensor([0, tids.numel()], dtype=torch.int64).cuda()
+    sub = rii.rii_adc_scan_subset(d["index"], lut[:1].contiguous(), tids, toff, tids.numel(), 50)
+    torch.cuda.synchronize()
+    assert np.array_equal(d["index"].get_codes(), codes)
+    for i in range(8):
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], codes, 50)
+        assert np.array_equal(t2n(lin[0])[i], ref[0]) and np.array_equal(t2n(lin[1])[i], ref[1])
+    ref = oracle_lib.linear_scan(d["lut_ref"][0], codes, 50, S=t2n(tids))
+    assert np.array_equal(t2n(sub[0])[0], ref[0]) and np.array_equal(t2n(sub[1])[0], ref[1])
 
 
 def test_determinism(rii, idx32):
