@@ -187,9 +187,10 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
     if (Q >= 4) {
       // Many queries: the seeding blocks no longer run side by side, each costs a table fill, and
       // on a small array 256 of them per query would score all of it once more.  A thirty-second
-      // of the rows is enough for a useful bound, as long as there are at least topk wave minima.
+      // of the rows, and never more than 128 blocks, is enough for a useful bound, as long as
+      // there are at least topk wave minima.
       const int64_t least = std::min<int64_t>(tiles, (topk + kScanThreads / 64 - 1) / (kScanThreads / 64) + 1);
-      pre_blocks = (int)std::max<int64_t>(least, std::min<int64_t>(pre_blocks, tiles / 32));
+      pre_blocks = (int)std::max<int64_t>(least, std::min<int64_t>(std::min(pre_blocks, kPrepassBlocks / 2), tiles / 32));
     }
     // The single-query kernel seeds the bound itself when all its blocks run at once and a query
     // has at least topk of them (rotated form only); otherwise a separate pass does it.
