@@ -105,7 +105,7 @@ int set_lds0(Kern kern, size_t bytes) {
 // in total when the batch is small, never chunks shorter than kMinTiles tiles.
 void scan_chunks(int Q, int64_t max_rows, int64_t* nchunks_out, int64_t* chunk_rows_out) {
   const int64_t tile = (int64_t)kScanThreads * kRowsPerLane;
-  int64_t want = (kWantBlocks + Q - 1) / Q;
+  int64_t want = std::max<int64_t>(1, kWantBlocks / Q);  // rounded down: one block over a full round costs a second round
   int64_t most = std::max<int64_t>(1, (max_rows + kMinTiles * tile - 1) / (kMinTiles * tile));
   int64_t nchunks = std::min<int64_t>(std::min(want, most), 65535);
   int64_t chunk_rows = (max_rows + nchunks - 1) / nchunks;
@@ -128,6 +128,8 @@ bool plan_batch(int M, int Q, int64_t rows, int topk, int64_t* nchunks_out, int6
     const int64_t want = (kBatchWantBlocks + groups - 1) / groups;
     const int64_t most = std::max<int64_t>(1, rows / (kBatchMinTiles * tile));
     nchunks = std::min<int64_t>(std::min(want, most), 65535);
+    // whole rounds of blocks (one block per CU): a part-filled last round takes as long as a full one
+    if (groups * nchunks > kWantBlocks) nchunks = std::max<int64_t>(1, groups * nchunks / kWantBlocks * kWantBlocks / groups);
     chunk_rows = (rows + nchunks - 1) / nchunks;
     chunk_rows = (chunk_rows + tile - 1) / tile * tile;
     nchunks = (rows + chunk_rows - 1) / chunk_rows;
