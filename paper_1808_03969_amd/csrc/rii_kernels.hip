@@ -232,7 +232,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
                                k_tau0<32, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
                    k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a4); } break;
       }
-    } else if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2) {
+    } else if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2 && topk > kWaveK4) {
       // Large batch with topk beyond the four-query kernel's reach: two queries per block
       // (k_scan_w2), every block owning its queries' whole scan, and a single-query block for an
       // odd one left over, addressed as query 0 of argument arrays shifted by Q - 1.
@@ -329,7 +329,7 @@ int rii_scan_linear_plan(const rii_index_t* idx, int Q, int topk, int* queries_p
   if (topk <= kWaveK && plan_batch(idx->M, Q, idx->N, topk, &bchunks, &brows)) {
     *queries_per_block = 4;
     *row_chunks = bchunks;
-  } else if (topk <= kWaveK && rot_m(idx->M) && nchunks == 1 && Q >= 2) {
+  } else if (topk <= kWaveK && rot_m(idx->M) && nchunks == 1 && Q >= 2 && topk > kWaveK4) {
     *queries_per_block = 2;
     *row_chunks = 1;
   } else {

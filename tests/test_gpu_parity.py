@@ -89,7 +89,8 @@ def test_lut_bit_exact(name, rii, request):
 
 
 # ---------------------------------------------------------------- Alg. 1, whole database
-@pytest.mark.parametrize("name,topk", [("idx8", 10), ("idx16", 100), ("idx32", 100), ("idx32", 1), ("idx16", 1024), ("idx32", 128), ("idx32", 129), ("idx16", 2), ("idx16", 65)])
+@pytest.mark.parametrize("name,topk", [("idx8", 10), ("idx16", 100), ("idx32", 100), ("idx32", 1), ("idx16", 1024), ("idx32", 128), ("idx32", 129), ("idx16", 2), ("idx16", 65),
+                                       ("idx8", 128)])  # (one chunk, 100 < topk <= 128: the two-queries-per-block kernel)
 def test_linear_scan(name, topk, rii, oracle_lib, request):
     d = request.getfixturevalue(name)
     ids, dist = rii.rii_adc_scan_linear(d["index"], lut_dev(rii, d), topk)
