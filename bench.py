@@ -41,10 +41,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # size).  Reported only for the exact configuration they were measured on.
 MEASURED_TRAFFIC = {
     ("c5_billion_shard", 100_000_000, 10_000): {
-        # k_scan_w, one query: 797,119 KiB fetched x 2, 135 KiB written
-        "single": 797_119 * 2.0 * 1024 + 135 * 1024,
-        # k_scan_w4, 10,000 queries: 1,130,878,109 KiB fetched x 2, 10,770 KiB written
-        "batched": 1_130_878_109 * 2.0 * 1024 + 10_770 * 1024,
+        # k_scan_w, one query: 797,079 KiB fetched x 2, 1,155 KiB written
+        "single": 797_079 * 2.0 * 1024 + 1_155 * 1024,
+        # k_scan_w4, 10,000 queries: 974,001,968 KiB fetched x 2, 10,593 KiB written
+        "batched": 974_001_968 * 2.0 * 1024 + 10_593 * 1024,
     },
 }
 
