@@ -11,14 +11,22 @@ on), with every input already resident in HBM:
     -> subset (gathered) scan + top-R -> the Alg. 3 query procedure on the whole database.
 
 It prints ONE JSON line.  `value` is the number of PQ codes scored per second over the whole
-step.  `roofline` is the one-query-per-pass linear scan (k_scan_w: M algorithmic bytes per code, bound
-by HBM; with early abandoning over the two-plane layout of M = 32 it moves about half of them, see
-`moved_gbs`), timed with HIP events recorded around that kernel on its stream;
-`roofline_batched` is the batched launch of the timed steps (k_scan_w4: four queries share each
+step.  Three roofline objects:
+
+`roofline` -- the one-query-per-launch linear scan of the configuration's own data (k_scan_w,
+bound by HBM), timed with HIP events recorded around that kernel on its stream.  `frac` is the
+rate of bytes the kernel really moved (`traffic`, from the tallies the kernel keeps in the same
+launches: first plane streamed, second-plane lines fetched on demand or streamed) against the
+8 TB/s peak, so it cannot exceed 1; the method's own M bytes per code are reported beside it
+(`algorithmic_bytes_per_launch`, `algorithmic_gbs`, `moved_over_algorithmic`).
+`roofline_no_pruning` -- the same kernel over N independent uniform code bytes, where half-way
+abandoning saves nothing and the kernel streams every byte: moved = algorithmic.
+`roofline_batched` -- the batched launch of the timed steps (k_scan_w4: four queries share each
 code byte, so the bound is the LDS look-up rate; `achieved` counts the look-ups the kernel really
-made -- it abandons part of them -- and the ceiling is measured live with the library's
-look-up-only kernel).  `cpu_baseline` is the CPU oracle's linear scan timed single-threaded on a
-bounded sample of the same codes (and, beside it, on all host threads with one query each).
+made -- it abandons part of them -- and `peak` is the best rate the library's look-up-only kernel
+reaches over several occupancies, measured in the same run).
+`cpu_baseline` is the CPU oracle's linear scan timed single-threaded on a bounded sample of the
+same codes (and, beside it, on all host threads with one query each).
 """
 from __future__ import annotations
 
@@ -35,22 +43,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM-side bytes per launch from the rocprofv3 PMC runs summarised in
-# profiles/k_scan_w_k_scan_w4_c5_hbm_traffic_pmc.txt (FETCH_SIZE
-# x 2.000 + WRITE_SIZE x 1.000 KiB, the factors found with a plain streaming kernel of known
-# size).  Reported only for the exact configuration they were measured on.
-MEASURED_TRAFFIC = {
-    ("c5_billion_shard", 100_000_000, 10_000): {
-        # k_scan_w, one query: 797,079 KiB fetched x 2, 1,155 KiB written
-        "single": 797_079 * 2.0 * 1024 + 1_155 * 1024,
-        # k_scan_w4, 10,000 queries: 974,001,968 KiB fetched x 2, 10,593 KiB written
-        "batched": 974_001_968 * 2.0 * 1024 + 10_593 * 1024,
-    },
-}
-
-# LDS look-up ceiling from unit counts: 256 CUs x 128 B/clk of LDS bandwidth at 2.4 GHz; an
-# 8-byte look-up (ds_read_b64) therefore at most 16 lanes per clock and CU.
-LDS_SPEC_LOOKUPS_PER_S = 256 * 16 * 2.4e9
+# Occupancies the LDS look-up ceiling is measured at: (blocks, threads per block, LDS bytes per
+# block).  The ceiling reported is the best of them.
+LDS_CEILING_SHAPES = [(256, 1024, 150 * 1024), (512, 1024, 64 * 1024), (1024, 1024, 64 * 1024), (2048, 512, 64 * 1024)]
 
 
 def log(*a):
@@ -84,6 +79,9 @@ def main():
     ap.add_argument("--subset", type=int, default=1_000_000, help="|S| of the subset scan")
     ap.add_argument("--nprobe", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-uniform-leg", action="store_true", help="skip roofline_no_pruning (the scan of uniform random codes)")
+    ap.add_argument("--plane-variants", action="store_true",
+                    help="also time the one-query scan with the second plane forced on demand / forced streamed")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain streaming kernel of known size (1 GiB read + 1 GiB written) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -158,7 +156,8 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     stage_ms /= args.steps
-    slices, abandoned = binding.rii_index_read_scan_counters(index)
+    counters = binding.rii_index_read_scan_counters(index)
+    slices, abandoned = counters[0], counters[1]
     rii.rii_index_set_scan_events(index, None, None)
 
     # codes scored in one step
@@ -171,33 +170,75 @@ def main():
     scored = Q * N + Q * S + (probed + probed_query + 2 * Q * K if K else 0)
     value = scored / (ms_per_step * 1e-3)
 
-    # one query per pass: the plain HBM-roofline number for the scan kernel
-    rii.rii_index_set_scan_events(index, ev.start.value, ev.stop.value)
-    single = []
-    for i in range(12):
-        rii.rii_adc_scan_linear(index, lut[i % Q:i % Q + 1], R)
+    def one_query_leg(idx, n_rows, lut1, what, launches=12, plane_fetch=None):
+        """One query per launch over `idx`: launch time from the events around the kernel, bytes
+        moved from the kernel's own tallies of the same launches."""
+        if plane_fetch is not None:
+            idx.set_option(binding.RII_OPT_PLANE_FETCH, plane_fetch)
+        rii.rii_index_set_scan_events(idx, ev.start.value, ev.stop.value)
+        for i in range(2):                                   # warm-up (also sizes the scratch)
+            rii.rii_adc_scan_linear(idx, lut1[i % len(lut1):i % len(lut1) + 1], R)
         torch.cuda.synchronize()
-        single.append(ev.elapsed_ms())
-    rii.rii_index_set_scan_events(index, None, None)
-    single_ms = float(np.mean(single[2:]))
+        binding.rii_index_read_scan_counters(idx)
+        ms = []
+        for i in range(launches):
+            rii.rii_adc_scan_linear(idx, lut1[i % len(lut1):i % len(lut1) + 1], R)
+            torch.cuda.synchronize()
+            ms.append(ev.elapsed_ms())
+        c = binding.rii_index_read_scan_counters(idx)
+        rii.rii_index_set_scan_events(idx, None, None)
+        if plane_fetch is not None:
+            idx.set_option(binding.RII_OPT_PLANE_FETCH, 0)
+        launch_ms = float(np.mean(ms))
+        algorithmic = float(n_rows) * M                      # M bytes per code and query pass
+        if M == 32:
+            # two planes of 16 bytes per row: the first is streamed whole; of the second, the
+            # 128-byte lines fetched on demand plus the 256-row wave-tiles streamed along
+            moved = n_rows * 16.0 + (128.0 * c[2] + 256 * 16.0 * c[3]) / launches
+        else:
+            moved = algorithmic
+        moved = min(moved, algorithmic)                      # (rows re-read at block seams are cache hits)
+        gbs = moved / (launch_ms * 1e-3) / 1e9
+        return {
+            "bound": "hbm", "kernel": f"k_scan_w<{M},linear>, one query per launch, {what}",
+            "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "traffic": moved, "traffic_source": "kernel tallies of the timed launches (second-plane lines and tiles)"
+                                               if M == 32 else "every code byte is read once",
+            "launch_ms": round(launch_ms, 4), "launch_ms_min_max": [round(min(ms), 4), round(max(ms), 4)],
+            "algorithmic_bytes_per_launch": algorithmic,
+            "algorithmic_gbs": round(algorithmic / (launch_ms * 1e-3) / 1e9, 1),
+            "moved_over_algorithmic": round(moved / algorithmic, 4),
+            "blocks_streaming_both_planes": int(c[4] // launches), "blocks_fetching_on_demand": int(c[5] // launches),
+            "codes_per_s": round(n_rows / (launch_ms * 1e-3), 1),
+        }
 
+    # one query per pass: the HBM-roofline number for the scan kernel, on the configuration's own data ...
+    roofline = one_query_leg(index, N, lut, f"{cfg.name} data")
     scan_avg_ms = float(np.mean(scan_ms))
-    traffic = MEASURED_TRAFFIC.get((cfg.name, N, Q), {})
-    single_gbs = N * M / (single_ms * 1e-3) / 1e9   # M algorithmic bytes per code and query pass
-    roofline = {
-        "bound": "hbm", "kernel": f"k_scan_w<{M},linear> (seeds its bound itself), one query per launch",
-        "achieved": round(single_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(single_gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get("single"),
-        "launch_ms": round(single_ms, 4), "algorithmic_bytes_per_launch": float(N) * M,
-        "codes_per_s": round(N / (single_ms * 1e-3), 1),
-    }
-    if traffic.get("single"):
-        # For M = 32 the kernel skips the second 16-byte plane of slices it settles after 16
-        # look-ups, so it moves fewer bytes than the algorithmic count and `frac` can exceed 1;
-        # the rate at which it really moves bytes is reported beside it.
-        moved = traffic["single"] / (single_ms * 1e-3) / 1e9
-        roofline["moved_gbs"] = round(moved, 1)
-        roofline["moved_frac_of_peak"] = round(moved / HBM_PEAK_GBS, 4)
+    # ... and on independent uniform code bytes, where half-way abandoning saves nothing
+    no_pruning = None
+    if not args.no_uniform_leg:
+        t0 = time.time()
+        uni = rii.Index(w["cb"])
+        if M == 32:
+            uni.set_option(binding.RII_OPT_GATHER_COPY, 0)   # this index is only ever scanned in sequence
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(7000 + cfg.c)
+        for r0 in range(0, N, 10_000_000):
+            n = min(N, r0 + 10_000_000) - r0
+            uni.add(torch.randint(0, 256, (n, M), dtype=torch.uint8, device="cuda", generator=gen))
+        torch.cuda.synchronize()
+        log(f"{N} uniform random codes stored in {time.time() - t0:.1f}s")
+        no_pruning = one_query_leg(uni, N, lut, "independent uniform code bytes")
+        if args.plane_variants and M == 32:
+            no_pruning["forced_on_demand_ms"] = one_query_leg(uni, N, lut, "", plane_fetch=1)["launch_ms"]
+            no_pruning["forced_both_planes_ms"] = one_query_leg(uni, N, lut, "", plane_fetch=2)["launch_ms"]
+        uni.close()
+    if args.plane_variants and M == 32:
+        roofline["forced_on_demand_ms"] = one_query_leg(index, N, lut, "", plane_fetch=1)["launch_ms"]
+        both = one_query_leg(index, N, lut, "", plane_fetch=2)
+        roofline["forced_both_planes_ms"], roofline["forced_both_planes_frac"] = both["launch_ms"], both["frac"]
+
     # The batched launch: look-ups, not bytes, are what bounds it.
     batched = None
     qpb, row_chunks = binding.rii_scan_linear_plan(index, Q, R)
@@ -205,26 +246,30 @@ def main():
         groups = (Q + 3) // 4
         lookups = float(groups) * N * M            # one 8-byte LDS read per code byte and group of four queries
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ceil_ms = []
-        for _ in range(4):
-            a.record()
-            n_lk = binding.rii_bench_lds_lookups(8, 256, 4000, 150 * 1024)   # one block per CU, as k_scan_w4 runs
-            b.record()
-            torch.cuda.synchronize()
-            ceil_ms.append(a.elapsed_time(b))
-        ceiling = n_lk / (min(ceil_ms[1:]) * 1e-3)
+        shapes = {}
+        for blocks, threads, lds in LDS_CEILING_SHAPES:
+            iters = max(1, 4000 * 256 * 1024 // (blocks * threads))
+            best = 0.0
+            for _ in range(3):
+                a.record()
+                n_lk = binding.rii_bench_lds_lookups(8, blocks, threads, iters, lds)
+                b.record()
+                torch.cuda.synchronize()
+                best = max(best, n_lk / (a.elapsed_time(b) * 1e-3))
+            shapes[f"{blocks}x{threads}thr,{lds // 1024}KB"] = round(best / 1e9, 1)
+        ceiling = max(shapes.values()) * 1e9
         # look-ups the kernel actually made: a slice is 64 rows x M look-ups, an abandoned one stops after M/2
         executed = 64.0 * (slices * M - abandoned * (M // 2)) / args.steps
         ach = executed / (scan_avg_ms * 1e-3)
         batched = {
             "bound": "lds", "kernel": f"k_scan_w4<{M}>, {Q} queries per launch, {row_chunks} row chunk(s)", "achieved": round(ach / 1e9, 1),
             "peak": round(ceiling / 1e9, 1), "unit": "G look-ups/s", "frac": round(ach / ceiling, 4),
-            "peak_source": "measured live: rii_bench_lds_lookups(width 8, 256 blocks x 1024 threads)",
-            "spec_peak": round(LDS_SPEC_LOOKUPS_PER_S / 1e9, 1), "frac_of_spec": round(ach / LDS_SPEC_LOOKUPS_PER_S, 4),
+            "peak_source": "best of the look-up-only kernel (rii_bench_lds_lookups, 8-byte reads) over the launch shapes listed",
+            "peak_by_launch_shape": shapes,
             "lookups_executed_per_launch": executed, "lookups_algorithmic_per_launch": lookups,
             "abandoned_slice_fraction": round(abandoned / max(slices, 1), 4),
             "algorithmic_lookup_rate": round(lookups / (scan_avg_ms * 1e-3) / 1e9, 1),
-            "traffic": traffic.get("batched"), "launch_ms": round(scan_avg_ms, 3),
+            "launch_ms": round(scan_avg_ms, 3),
             "algorithmic_bytes_per_launch": float(Q) * N * M,
             "algorithmic_gbs": round(float(Q) * N * M / (scan_avg_ms * 1e-3) / 1e9, 1),
         }
@@ -283,11 +328,12 @@ def main():
         "stage_ms": {"lut": round(stage_ms[0], 3), "linear": round(stage_ms[1], 3), "coarse": round(stage_ms[2], 3),
                      "ivf": round(stage_ms[3], 3), "subset": round(stage_ms[4], 3), "query": round(stage_ms[5], 3)},
         "codes_scored_per_step": scored,
-        "hbm_frac_of_peak": roofline["frac"],
         "roofline": roofline,
+        "roofline_no_pruning": no_pruning,
         "roofline_batched": batched,
         "cpu_baseline": cpu,
-        "index": {"paper_bytes": info["paper_bytes"], "device_bytes": info["device_bytes"], "setup_s": w["timings"]},
+        "index": {"paper_bytes": info["paper_bytes"], "device_bytes": info["device_bytes"],
+                  "device_over_paper": round(info["device_bytes"] / info["paper_bytes"], 3), "setup_s": w["timings"]},
     }
     print(json.dumps(line), flush=True)
 

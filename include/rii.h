@@ -23,7 +23,9 @@
  *   - Online calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream); outputs are valid once the stream has been synchronised.  A handle keeps
  *     scratch memory that the online calls reuse, so calls on one handle must be issued on
- *     one stream at a time.
+ *     one stream at a time.  A call that needs more scratch than the handle holds frees and
+ *     re-allocates it first, which waits for the device; rii_index_reserve_workspace sizes it
+ *     ahead of time.
  *   - Results are ordered by (distance, identifier) ascending; distances are squared
  *     (Eq. (2)), fp32, accumulated over sub-spaces in ascending order.  When fewer than R
  *     candidates exist the tail is filled with identifier -1 and distance +infinity.
@@ -92,7 +94,8 @@ int rii_index_create(const float* codebooks, int D, int M, int Ks, rii_index_t**
  * Device memory held per code: M bytes, 2 M for M = 32 (which keeps the codes in two layouts, one
  * for sequential and one for gathered scans), plus M + 8 once posting lists are installed
  * (list-ordered copy, identifier, a(n)); rii_index_info reports the total.
- * Synchronous. */
+ * Synchronous.  If the codes were stored but re-listing them failed (RII_ERR_OOM, RII_ERR_DEVICE), the
+ * index keeps the codes and is left without posting lists. */
 int rii_index_add(rii_index_t* index, const uint8_t* codes, int64_t n, int mem);
 
 /* Install coarse centres and posting lists made elsewhere (Sec. 4.1: C and W).
@@ -121,6 +124,28 @@ int rii_index_reconfigure(rii_index_t* index, int K, int iters, uint64_t seed);
 /* The threshold theta of Alg. 3 (default 0: always the inverted index when lists exist). */
 int rii_index_set_threshold(rii_index_t* index, int64_t theta);
 
+/* Options of a handle (rii_index_set_option).  None of them changes any result.
+ *   RII_OPT_PLANE_FETCH   how the one-query whole-database scan reads an M = 32 code array, which is
+ *                         stored as two planes of 16 bytes per row: 0 (default) every block decides
+ *                         from its first rows whether to stream both planes or to fetch second
+ *                         halves only for rows still within the bound after 16 look-ups; 1 always
+ *                         on demand; 2 always both planes.
+ *   RII_OPT_GATHER_COPY   M = 32 only: 1 (default) keeps the codes a second time as whole 32-byte
+ *                         rows, which is what scans over target identifiers gather from (one memory
+ *                         line per row); 0 drops that copy (N M bytes less; such scans then gather
+ *                         the two halves of a row from the two planes).  Must be set before the
+ *                         first rii_index_add. */
+enum { RII_OPT_PLANE_FETCH = 1, RII_OPT_GATHER_COPY = 2 };
+int rii_index_set_option(rii_index_t* index, int option, int64_t value);
+
+/* Size the handle's scratch once, so that no later online call has to grow it (growing it frees and
+ * allocates device memory, which waits for the device): enough for every online call with at most
+ * Q queries, topk results and, for the inverted index, nprobe lists per query (for rii_query:
+ * the largest ceil(K L / |S|) any query of a batch can reach, at most K; 0 if the inverted index
+ * is not used).  max_targets is accepted for symmetry with the scans and does not change the
+ * size.  Call it again after rii_index_add / reconfigure changed N or K.  Synchronous. */
+int rii_index_reserve_workspace(rii_index_t* index, int Q, int topk, int64_t max_targets, int nprobe);
+
 /* Choose theta by measurement (Sec. 4.2, "Selection": the threshold is found by running both
  * search methods for several settings when the structure is built and fitting a line).  For
  * target-set sizes |S| = 64, 256, ... up to max_targets (0 = N) this times, on the GPU and for a
@@ -132,18 +157,6 @@ int rii_index_set_threshold(rii_index_t* index, int64_t theta);
  * batch size nq the caller intends to use.  Needs posting lists.  Synchronous. */
 int rii_index_calibrate_threshold(rii_index_t* index, int64_t L, int topk, int nq, int64_t max_targets,
                                   uint64_t seed, int64_t* theta_out);
-
-/* Measurement aid: while two hipEvent_t (passed as void*) are set, every rii_adc_scan_linear
- * call (and the linear-scan branch of rii_query) records `start_event` right before and
- * `stop_event` right after the kernel that streams the code array (Alg. 1, the loop over s),
- * on the call's stream.  Pass NULL, NULL to switch it off.  The caller owns the events. */
-int rii_index_set_scan_events(rii_index_t* index, void* start_event, void* stop_event);
-
-/* Measurement aid: while the scan events are set, the batched linear-scan kernel counts the
- * slices (64 rows x one group of four queries, i.e. 64 x M table look-ups) it scored and how many
- * of them it abandoned half-way (then only M/2 look-ups each were made).  Returns the two
- * counts accumulated since the last call and resets them.  Synchronous (waits for the device). */
-int rii_index_read_scan_counters(rii_index_t* index, uint64_t* slices_scored, uint64_t* slices_abandoned);
 
 /* info_out[0..7] = N, D, M, Ks, K (0 without lists), theta, bytes of the paper's data
  * structure ((N+K) M + 4 N, Sec. 4.1), device bytes actually held by the handle. */
@@ -248,27 +261,6 @@ int rii_rotate(const float* R, int D, const float* x, int64_t n, float* y, void*
  *   codes device [n][M]; coarse device [K][M]; assign_out device [n] int32 (written). */
 int rii_assign(const rii_index_t* index, const uint8_t* codes, int64_t n, const uint8_t* coarse, int K,
                int32_t* assign_out, void* stream);
-
-/* ------------------------------------------------------------------ measurement -------- */
-
-/* Launch shape rii_adc_scan_linear uses for a batch of Q queries on this index (so that a
- * benchmark can name the kernel it timed): *queries_per_block = 4, 2 or 1 queries sharing one
- * pass over the codes (Alg. 1 run for several queries at once; results are per query);
- * *row_chunks = blocks that share one query group's rows.  Host call, no GPU work. */
-int rii_scan_linear_plan(const rii_index_t* index, int Q, int topk, int* queries_per_block, int64_t* row_chunks);
-
-/* LDS look-up ceiling of the scan kernels' inner loop, for the roofline of the batched scan
- * (Sec. 3: a distance is M table look-ups; with several queries per pass these, not the code
- * stream, bound the kernel).  Runs `blocks` blocks of 1024 threads; every lane performs
- * iters * 32 dependent-free look-ups (one byte-permute, one LDS read of `width` bytes at a
- * conflict-free pseudo-random address in a 64 KB table, one add per component) and nothing
- * else; no global memory traffic inside the loop.
- *   width 4 or 8 (ds_read_b32 / ds_read_b64 with 32-bit adds per component) or 64 (ds_read_b64
- *   with one 64-bit integer add per look-up); lds_bytes >= 65536 sizes the block's LDS
- *   allocation (and thereby blocks per CU); sink device uint32 [1] (written only to keep the
- *   loop alive).  The caller times the call with events on `stream`.
- * Look-ups performed = blocks * 1024 * 32 * iters. */
-int rii_bench_lds_lookups(int width, int blocks, int iters, int lds_bytes, uint32_t* sink, void* stream);
 
 #ifdef __cplusplus
 }

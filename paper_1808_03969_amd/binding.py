@@ -15,11 +15,14 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librii_hip.so")
-_HEADER = os.path.join(os.path.dirname(_HERE), "include", "rii.h")
+_INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
+_HEADERS = [os.path.join(_INCLUDE, "rii.h"), os.path.join(_INCLUDE, "rii_bench.h")]
 _lib = None
 
 RII_MEM_HOST, RII_MEM_DEVICE = 0, 1
 RII_MAX_TOPK, RII_MAX_SORT = 1024, 16384
+RII_OPT_PLANE_FETCH, RII_OPT_GATHER_COPY = 1, 2
+RII_SCAN_COUNTERS = 8
 
 
 class RiiError(RuntimeError):
@@ -34,10 +37,12 @@ def library_path() -> str:
 
 
 def declared_symbols() -> list[str]:
-    """Names of the functions ``include/rii.h`` declares."""
-    text = open(_HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rii_[a-z_]+)\s*\(", text)))
+    """Names of the functions the headers under ``include/`` declare."""
+    names = set()
+    for h in _HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b(rii_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def load_library():
@@ -163,6 +168,13 @@ class Index:
 
     def reconfigure(self, K: int, iters: int = 20, seed: int = 0):
         _check(self._lib.rii_index_reconfigure(self._h, K, iters, ctypes.c_uint64(seed)), "rii_index_reconfigure")
+
+    def set_option(self, option: int, value: int):
+        _check(self._lib.rii_index_set_option(self._h, option, i64(value)), "rii_index_set_option")
+
+    def reserve_workspace(self, Q: int, topk: int, max_targets: int = 0, nprobe: int = 0):
+        _check(self._lib.rii_index_reserve_workspace(self._h, Q, topk, i64(max_targets), nprobe),
+               "rii_index_reserve_workspace")
 
     def set_threshold(self, theta: int):
         _check(self._lib.rii_index_set_threshold(self._h, i64(theta)), "rii_index_set_threshold")
@@ -318,11 +330,11 @@ def rii_assign(index: Index, codes: torch.Tensor, coarse: torch.Tensor) -> torch
 
 
 def rii_index_read_scan_counters(index: Index):
-    """(slices scored, slices abandoned half-way) by the batched scan since the last call; resets them."""
-    a, b = ctypes.c_uint64(0), ctypes.c_uint64(0)
-    _check(load_library().rii_index_read_scan_counters(index.handle, ctypes.byref(a), ctypes.byref(b)),
-           "rii_index_read_scan_counters")
-    return a.value, b.value
+    """The tallies of the whole-database scan kernels since the last call (a list of
+    RII_SCAN_COUNTERS integers, see rii_bench.h); resets them."""
+    out = (ctypes.c_uint64 * RII_SCAN_COUNTERS)()
+    _check(load_library().rii_index_read_scan_counters(index.handle, out), "rii_index_read_scan_counters")
+    return [int(v) for v in out]
 
 
 def rii_scan_linear_plan(index: Index, Q: int, topk: int):
@@ -333,13 +345,13 @@ def rii_scan_linear_plan(index: Index, Q: int, topk: int):
     return qpb.value, chunks.value
 
 
-def rii_bench_lds_lookups(width: int, blocks: int, iters: int, lds_bytes: int = 98 * 1024) -> int:
+def rii_bench_lds_lookups(width: int, blocks: int, threads: int, iters: int, lds_bytes: int = 98 * 1024) -> int:
     """Measurement aid: launch the LDS look-up ceiling kernel on the current stream (time it with
     events); returns the number of look-ups it performs."""
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    _check(load_library().rii_bench_lds_lookups(width, blocks, iters, lds_bytes, _dp(sink), _stream()),
+    _check(load_library().rii_bench_lds_lookups(width, blocks, threads, iters, lds_bytes, _dp(sink), _stream()),
            "rii_bench_lds_lookups")
-    return blocks * 1024 * 32 * iters
+    return blocks * threads * 32 * iters
 
 
 def rii_index_set_scan_events(index: Index, start_event, stop_event):

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "rii_internal.h"
+#include "rii_bench.h"
 
 extern "C" int rii_internal_sym_table(const rii_index* idx, hipStream_t st);
 extern "C" int rii_internal_assign(const rii_index* idx, const uint8_t* codes, int64_t n, int64_t rot_base, int64_t plane,
@@ -27,6 +28,8 @@ extern "C" int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, int64_t
                                       hipStream_t st);
 
 namespace {
+
+constexpr int kCounters = 8;  // entries of rii_index::d_scan_counters (ScanArgs::counters)
 
 // byte distance between the two planes of a stored array of `rows` rows (see rii_index)
 int64_t plane_for(int M, int64_t rows) { return M == 32 ? rows * 16 : 0; }
@@ -299,24 +302,40 @@ int rii_index_set_threshold(rii_index_t* idx, int64_t theta) {
 int rii_index_set_scan_events(rii_index_t* idx, void* start_event, void* stop_event) {
   if (!idx || ((start_event == nullptr) != (stop_event == nullptr))) return RII_ERR_INVALID_ARG;
   if (start_event && !idx->d_scan_counters) {
-    RII_HIP(hipMalloc(&idx->d_scan_counters, 2 * sizeof(unsigned long long)));
-    RII_HIP(hipMemset(idx->d_scan_counters, 0, 2 * sizeof(unsigned long long)));
+    RII_HIP(hipMalloc(&idx->d_scan_counters, kCounters * sizeof(unsigned long long)));
+    RII_HIP(hipMemset(idx->d_scan_counters, 0, kCounters * sizeof(unsigned long long)));
   }
   idx->ev_start = start_event;
   idx->ev_stop = stop_event;
   return RII_OK;
 }
 
-int rii_index_read_scan_counters(rii_index_t* idx, uint64_t* slices_scored, uint64_t* slices_abandoned) {
-  if (!idx || !slices_scored || !slices_abandoned) return RII_ERR_INVALID_ARG;
-  *slices_scored = *slices_abandoned = 0;
+int rii_index_read_scan_counters(rii_index_t* idx, uint64_t* counters_out) {
+  if (!idx || !counters_out) return RII_ERR_INVALID_ARG;
+  for (int i = 0; i < kCounters; ++i) counters_out[i] = 0;
   if (!idx->d_scan_counters) return RII_OK;
-  unsigned long long h[2] = {0, 0};
+  unsigned long long h[kCounters] = {};
   RII_HIP(hipMemcpy(h, idx->d_scan_counters, sizeof(h), hipMemcpyDeviceToHost));  // waits for earlier work
   RII_HIP(hipMemset(idx->d_scan_counters, 0, sizeof(h)));
-  *slices_scored = h[0];
-  *slices_abandoned = h[1];
+  for (int i = 0; i < kCounters; ++i) counters_out[i] = h[i];
   return RII_OK;
+}
+
+int rii_index_set_option(rii_index_t* idx, int option, int64_t value) {
+  if (!idx) return RII_ERR_INVALID_ARG;
+  switch (option) {
+    case RII_OPT_PLANE_FETCH:
+      if (value < 0 || value > 2) return RII_ERR_INVALID_ARG;
+      idx->plane_fetch = (int)value;
+      return RII_OK;
+    case RII_OPT_GATHER_COPY:
+      if (value != 0 && value != 1) return RII_ERR_INVALID_ARG;
+      if (idx->cap > 0 && (value != 0) != idx->keep_rows_copy) return RII_ERR_INVALID_ARG;  // layout is fixed once codes are stored
+      idx->keep_rows_copy = value != 0;
+      return RII_OK;
+    default:
+      return RII_ERR_INVALID_ARG;
+  }
 }
 
 // ---- threshold calibration (Sec. 4.2, "Selection")
@@ -327,6 +346,7 @@ int rii_index_calibrate_threshold(rii_index_t* idx, int64_t L, int topk, int nq,
   if (idx->N < 2 || idx->h_cb.size() != (size_t)idx->M * 256 * idx->Ds) return RII_ERR_INVALID_ARG;
   const int64_t N = idx->N;
   const int M = idx->M, D = idx->D, Ds = idx->Ds, K = idx->K;
+  if (L > N) L = N;  // a cap of N or more never cuts anything, and K * L stays far from overflow
   if (max_targets <= 0 || max_targets > N) max_targets = N;
   // queries: decoded stored codes (vectors the index can certainly answer), seeded choice
   std::vector<int64_t> rows = rii_host::sample_without_replacement(N, std::min<int64_t>(nq, N), seed);
@@ -407,7 +427,7 @@ int rii_index_info(const rii_index_t* idx, int64_t* info) {
   const int64_t N = idx->N, M = idx->M, K = idx->K;
   info[0] = N; info[1] = idx->D; info[2] = M; info[3] = idx->Ks; info[4] = K; info[5] = idx->theta;
   info[6] = (N + K) * M + 4 * N;
-  int64_t dev = (int64_t)M * 256 * idx->Ds * 4 + idx->cap * M * (idx->plane_codes ? 2 : 1) + (int64_t)idx->ws_bytes;
+  int64_t dev = (int64_t)M * 256 * idx->Ds * 4 + idx->cap * M * (idx->d_codes_rows != idx->d_codes ? 2 : 1) + (int64_t)idx->ws_bytes;
   if (idx->d_sym) dev += M * 256 * 256 * 4;
   if (K > 0) dev += K * M + (K + 1) * 8 + N * 4 /*ids*/ + N * 4 /*assign*/ + N * M /*list-ordered codes*/;
   info[7] = dev;
@@ -423,8 +443,10 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
   if (idx->N + n > idx->cap) {
     int64_t ncap = std::max<int64_t>(idx->N + n, idx->cap + idx->cap / 2);
     uint8_t* nb = nullptr;
-    // (M = 32 keeps the codes twice, as two planes and as whole rows: one allocation, rows last)
-    const size_t copies = plane_for(M, 1) ? 2 : 1;
+    // (M = 32 keeps the codes twice, as two planes and -- unless switched off -- as whole rows:
+    // one allocation, rows last)
+    const bool rows_copy = plane_for(M, 1) && idx->keep_rows_copy;
+    const size_t copies = rows_copy ? 2 : 1;
     if (hipMalloc(&nb, copies * (size_t)ncap * M) != hipSuccess) {
       (void)hipGetLastError();
       ncap = idx->N + n;
@@ -435,7 +457,7 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
       if (nplane) {  // each plane holds 16 bytes a row
         RII_HIP(hipMemcpy(nb, idx->d_codes, (size_t)idx->N * 16, hipMemcpyDeviceToDevice));
         RII_HIP(hipMemcpy(nb + nplane, idx->d_codes + idx->plane_codes, (size_t)idx->N * 16, hipMemcpyDeviceToDevice));
-        RII_HIP(hipMemcpy(nb + (size_t)ncap * M, idx->d_codes_rows, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
+        if (rows_copy) RII_HIP(hipMemcpy(nb + (size_t)ncap * M, idx->d_codes_rows, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
       } else {
         RII_HIP(hipMemcpy(nb, idx->d_codes, (size_t)idx->N * M, hipMemcpyDeviceToDevice));
       }
@@ -444,7 +466,8 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
     idx->d_codes = nb;
     idx->cap = ncap;
     idx->plane_codes = nplane;
-    idx->d_codes_rows = nplane ? nb + (size_t)ncap * M : nb;
+    idx->d_codes_rows = rows_copy ? nb + (size_t)ncap * M : nb;
+    idx->plane_rows = rows_copy ? 0 : nplane;
   }
   {
     // bring the new rows into stored form (row r rotated by r bytes when M is 8, 16 or 32)
@@ -472,16 +495,22 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
     // push every new identifier to the list of its nearest coarse centre; lists stay ascending
     // because new identifiers are larger than all stored ones
     std::vector<int32_t> assign(idx->N);
-    if (oldN > 0) RII_HIP(hipMemcpy(assign.data(), idx->d_assign, (size_t)oldN * 4, hipMemcpyDeviceToHost));
+    if (oldN > 0 && hipMemcpy(assign.data(), idx->d_assign, (size_t)oldN * 4, hipMemcpyDeviceToHost) != hipSuccess) {
+      (void)hipGetLastError();
+      drop_lists(idx);
+      return RII_ERR_DEVICE;
+    }
     std::vector<uint8_t> coarse = idx->h_coarse;
     const int K = idx->K;
+    // (from here on a failure leaves the index without posting lists rather than with lists
+    // that are shorter than the code array)
     int rc = assign_stored(idx, oldN, n, coarse.data(), K, assign.data() + oldN);
-    if (rc) return rc;
     std::vector<int64_t> off;
     std::vector<int32_t> ids;
-    rc = rii_host::build_csr(assign.data(), idx->N, K, off, ids);
-    if (rc) return rc;
-    return install_lists(idx, coarse.data(), K, off, ids, assign);
+    if (!rc) rc = rii_host::build_csr(assign.data(), idx->N, K, off, ids);
+    if (!rc) rc = install_lists(idx, coarse.data(), K, off, ids, assign);
+    if (rc) drop_lists(idx);
+    return rc;
   }
   return RII_OK;
 }

@@ -28,6 +28,9 @@ struct rii_index {
   // second time in that form (d_codes_rows, the tail of d_codes' allocation); for every other M
   // d_codes_rows is d_codes.
   int64_t plane_codes = 0, plane_list = 0, plane_coarse = 0;
+  int64_t plane_rows = 0;         // plane distance of d_codes_rows: 0 (whole rows) unless it is d_codes itself
+  bool keep_rows_copy = true;     // M = 32: keep the whole-row copy for gathered scans (RII_OPT_GATHER_COPY)
+  int plane_fetch = 0;            // RII_OPT_PLANE_FETCH: how the one-query scan reads the second plane
   uint8_t* d_codes = nullptr;     // [cap][M] codes in identifier order (the linear array), stored form
   uint8_t* d_codes_rows = nullptr;  // [cap][M] the same rows, rotated, never split (what the subset scan gathers from)
   uint8_t* d_coarse = nullptr;    // [K][M] coarse centres (PQ codes), plain
@@ -47,8 +50,7 @@ struct rii_index {
   // optional measurement aid: events recorded right before / after the linear-scan kernel
   void* ev_start = nullptr;
   void* ev_stop = nullptr;
-  // ... and, while the events are set, two device counters the batched scan kernel adds to:
-  // [0] slices (64 rows x one query group) it scored, [1] slices abandoned half-way
+  // ... and, while the events are set, device tallies the scan kernels add to (see ScanArgs::counters)
   unsigned long long* d_scan_counters = nullptr;
 };
 

@@ -20,9 +20,13 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <type_traits>
+#include <unordered_map>
 #include <vector>
 
 #include "rii_internal.h"
+#include "rii_bench.h"
 
 namespace {
 
@@ -62,35 +66,47 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 bool m_supported(int M) { return M >= 4 && M <= RII_MAX_M && M % 4 == 0; }
 
-template <typename Kern>
-int set_lds(Kern kern, size_t bytes) {
-  if (bytes > 48 * 1024) RII_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+// Per (device, kernel): the dynamic LDS size already granted with hipFuncSetAttribute, and whether
+// the kernel was checked to have no static LDS.  Looked up on every launch, written once per
+// kernel, so that the online calls make no runtime-attribute calls after their first launch.
+struct KernelLdsState {
+  size_t granted = 0;
+  bool at_zero = false;
+};
+std::mutex g_lds_mutex;
+std::unordered_map<uint64_t, KernelLdsState> g_lds_state;
+
+uint64_t lds_key(const void* kern) {
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  return (uint64_t)reinterpret_cast<uintptr_t>(kern) * 64u + (uint64_t)(dev & 63);
+}
+
+// Allow `kern` to be launched with `bytes` of dynamic LDS.  need_zero: the kernel addresses its
+// table as "LDS address 0", so it must not have static LDS in front of the dynamic allocation;
+// refuse to launch otherwise (checked once per kernel).
+int set_lds_impl(const void* kern, size_t bytes, bool need_zero) {
+  std::lock_guard<std::mutex> lock(g_lds_mutex);
+  KernelLdsState& st = g_lds_state[lds_key(kern)];
+  if (need_zero && !st.at_zero) {
+    hipFuncAttributes attr{};
+    RII_HIP(hipFuncGetAttributes(&attr, kern));
+    if (attr.sharedSizeBytes != 0) return RII_ERR_DEVICE;
+    st.at_zero = true;
+  }
+  if (bytes > 48 * 1024 && bytes > st.granted) {
+    RII_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    st.granted = bytes;
+  }
   return RII_OK;
 }
 
-// The kernels that address their table as "LDS address 0" must not have static LDS in front of
-// the dynamic allocation; refuse to launch otherwise.
 template <typename Kern>
-int require_table_at_lds_zero(Kern kern) {
-  hipFuncAttributes attr{};
-  RII_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
-  return attr.sharedSizeBytes == 0 ? RII_OK : RII_ERR_DEVICE;
-}
+int set_lds(Kern kern, size_t bytes) { return set_lds_impl(reinterpret_cast<const void*>(kern), bytes, false); }
 
-// set_lds for the kernels whose table must sit at LDS address 0 (checked once per kernel)
+// set_lds for the kernels whose table must sit at LDS address 0
 template <typename Kern>
-int set_lds0(Kern kern, size_t bytes) {
-  static int checked = -1;  // one instance per kernel type and address
-  static const void* which = nullptr;
-  if (checked < 0 || which != reinterpret_cast<const void*>(kern)) {
-    int rc = require_table_at_lds_zero(kern);
-    if (rc) return rc;
-    checked = 1;
-    which = reinterpret_cast<const void*>(kern);
-  }
-  return set_lds(kern, bytes);
-}
+int set_lds0(Kern kern, size_t bytes) { return set_lds_impl(reinterpret_cast<const void*>(kern), bytes, true); }
 
 #define DISPATCH_M(M, ...)                                  \
   switch (M) {                                              \
@@ -179,6 +195,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   const bool timed = mode == kLinear && idx->ev_start && idx->ev_stop && codes == idx->d_codes;
   a.counters = timed ? idx->d_scan_counters : nullptr;
+  a.plane_fetch = idx->plane_fetch;
   if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
   if (topk <= kWaveK) {
     // When a query's rows are split over several blocks, a short first pass over the leading
@@ -297,14 +314,26 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   return RII_OK;
 }
 
+// Minima of the bound-seeding pass: it only runs when the rows of a query are cut into chunks,
+// which launches of kSeedMaxQ or more queries never do.
+constexpr int kSeedMaxQ = 2048;
+size_t minima_bytes(int Q) { return (size_t)std::min(Q, kSeedMaxQ) * kPrepassBlocks * (kScanThreads / 64) * 4; }
+
 size_t scan_ws_bytes(int M, int Q, int64_t max_rows, int topk) {
   int64_t nchunks, chunk_rows;
   scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
   int64_t bchunks, brows;
   plan_batch(M, Q, max_rows, topk, &bchunks, &brows);
   const int64_t cap_chunks = std::max(nchunks, bchunks);
-  return kScanArrays * align_up((size_t)Q * 4, 256) + (size_t)Q * cap_chunks * topk * 8 +
-         (size_t)Q * kPrepassBlocks * (kScanThreads / 64) * 4 + 256;
+  return kScanArrays * align_up((size_t)Q * 4, 256) + (size_t)Q * cap_chunks * topk * 8 + minima_bytes(Q) + 256;
+}
+
+// The same for every batch of at most Q queries, at most max_rows rows and at most topk results:
+// a bound that grows with each argument (a batch's blocks per query times its queries stay
+// below Q + 4 kBatchWantBlocks + kWantBlocks whatever the launch shape is).
+size_t scan_ws_bound(int Q, int topk) {
+  return kScanArrays * align_up((size_t)Q * 4, 256) +
+         ((size_t)Q + 4 * kBatchWantBlocks + kWantBlocks + 8) * topk * 8 + minima_bytes(Q) + 256;
 }
 
 }  // namespace
@@ -339,22 +368,23 @@ int rii_scan_linear_plan(const rii_index_t* idx, int Q, int topk, int* queries_p
   return RII_OK;
 }
 
-int rii_bench_lds_lookups(int width, int blocks, int iters, int lds_bytes, uint32_t* sink, void* stream) {
+int rii_bench_lds_lookups(int width, int blocks, int threads, int iters, int lds_bytes, uint32_t* sink, void* stream) {
   if ((width != 4 && width != 8 && width != 64) || blocks < 1 || iters < 1 || !sink) return RII_ERR_INVALID_ARG;
+  if (threads < 64 || threads > kScanThreads || threads % 64 != 0) return RII_ERR_INVALID_ARG;
   if (lds_bytes < 65536 || lds_bytes > 160 * 1024) return RII_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (width == 64) {
     int rc = set_lds0(k_lds_lookups<64>, (size_t)lds_bytes);
     if (rc) return rc;
-    k_lds_lookups<64><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
+    k_lds_lookups<64><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
   } else if (width == 8) {
     int rc = set_lds0(k_lds_lookups<8>, (size_t)lds_bytes);
     if (rc) return rc;
-    k_lds_lookups<8><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
+    k_lds_lookups<8><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
   } else {
     int rc = set_lds0(k_lds_lookups<4>, (size_t)lds_bytes);
     if (rc) return rc;
-    k_lds_lookups<4><<<blocks, kScanThreads, (size_t)lds_bytes, st>>>(iters, sink);
+    k_lds_lookups<4><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
   }
   RII_HIP(hipGetLastError());
   return RII_OK;
@@ -400,7 +430,7 @@ int rii_adc_scan_subset(const rii_index_t* idx, const float* lut, int Q, const i
   int64_t rows = std::max<int64_t>(max_targets, 1);
   int rc = ensure_ws(idx, scan_ws_bytes(idx->M, Q, rows, topk));
   if (rc) return rc;
-  return launch_scan(idx, idx->d_codes_rows, 0, idx->N, lut, Q, kSubset, target_ids, target_offsets, rows, topk, ids, dist,
+  return launch_scan(idx, idx->d_codes_rows, idx->plane_rows, idx->N, lut, Q, kSubset, target_ids, target_offsets, rows, topk, ids, dist,
                      topk, nullptr, 0, idx->ws, static_cast<hipStream_t>(stream));
 }
 
@@ -522,6 +552,7 @@ int rii_adc_scan_ivf(const rii_index_t* idx, const float* lut, int Q, const int3
   if (nprobe < 1 || nprobe > idx->K) return RII_ERR_INVALID_ARG;
   if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
   if (topk > RII_MAX_TOPK || !m_supported(idx->M)) return RII_ERR_UNSUPPORTED;
+  if (L >= idx->N) L = 0;  // such a cap never cuts anything
   void* ws = nullptr;
   if ((L == 0 || !target_ids) && topk <= kWaveK) {
     int rc = ensure_ws(idx, ivf_ws_bytes(Q, nprobe, topk));
@@ -532,53 +563,73 @@ int rii_adc_scan_ivf(const rii_index_t* idx, const float* lut, int Q, const int3
                     dist, nullptr, 0, ws, static_cast<hipStream_t>(stream));
 }
 
-int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int32_t* target_ids,
-              const int64_t* target_offsets, int64_t max_targets, int64_t L, int32_t* ids, float* dist,
-              void* stream) {
-  if (!idx || !q || !ids || !dist || Q < 1 || topk < 1 || L < 1 || max_targets < 0) return RII_ERR_INVALID_ARG;
-  if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
-  if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
-  if (idx->N < 1) return RII_ERR_INVALID_ARG;
-  hipStream_t st = static_cast<hipStream_t>(stream);
+// Scratch layout of the query procedure: tables, per-query plan, probed lists, then the stage
+// scratch that the scan, the coarse ranking and the inverted-index scan use one after the other.
+struct QueryPlan {
+  int pmax = 1;          // most lists any inverted-index query of the batch can ask for
+  int64_t lin_rows = 1;  // most rows any linear-scan query of the batch can have
+  size_t lut_b = 0, plan_b = 0, probe_b = 0, ivf_b = 0, total = 0;
+};
+
+static int plan_query(const rii_index* idx, int Q, int topk, bool targets, int64_t max_targets, int64_t L,
+                      QueryPlan* p) {
   const int M = idx->M, K = idx->K;
   const bool has_lists = K > 0;
   // Largest number of lists any inverted-index query of this batch can ask for: such a query
   // has |S| >= max(theta, 1), and |S| = N when there is no target set.
-  int pmax = 1;
+  p->pmax = 1;
   if (has_lists) {
-    int64_t smin = target_ids ? std::max<int64_t>(idx->theta, 1) : idx->N;
-    int64_t p = ((int64_t)K * L + smin - 1) / smin;
-    pmax = (int)std::min<int64_t>(p, K);
-    if (pmax > RII_MAX_TOPK && K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
+    int64_t smin = targets ? std::max<int64_t>(idx->theta, 1) : idx->N;
+    int64_t pl = ((int64_t)K * L + smin - 1) / smin;
+    p->pmax = (int)std::min<int64_t>(pl, K);
+    if (p->pmax > RII_MAX_TOPK && K > RII_MAX_SORT) return RII_ERR_UNSUPPORTED;
   }
   // linear-scan queries have |S| < theta (and at most max_targets, N)
-  int64_t lin_rows = target_ids ? std::min<int64_t>(max_targets, idx->N) : idx->N;
+  int64_t lin_rows = targets ? std::min<int64_t>(max_targets, idx->N) : idx->N;
   if (has_lists && idx->theta > 0) lin_rows = std::min<int64_t>(lin_rows, idx->theta - 1);
   if (has_lists && idx->theta <= 0) lin_rows = 0;
-  if (!target_ids && has_lists && idx->N >= idx->theta) lin_rows = 0;
-  lin_rows = std::max<int64_t>(lin_rows, 1);
+  if (!targets && has_lists && idx->N >= idx->theta) lin_rows = 0;
+  p->lin_rows = std::max<int64_t>(lin_rows, 1);
+  p->lut_b = align_up((size_t)Q * M * 256 * 4, 256);
+  p->plan_b = align_up((size_t)Q * 4, 256);
+  p->probe_b = align_up((size_t)Q * p->pmax * 4, 256);
+  const size_t scan_b = align_up(scan_ws_bytes(M, Q, p->lin_rows, topk), 256);
+  const size_t coarse_b = has_lists ? align_up(coarse_ws_bytes(idx, Q, p->pmax), 256) : 0;
+  p->ivf_b = has_lists && topk <= kWaveK ? align_up(ivf_ws_bytes(Q, p->pmax, topk), 256) : 0;
+  p->total = p->lut_b + 2 * p->plan_b + p->probe_b + std::max(std::max(scan_b, coarse_b), p->ivf_b);
+  return RII_OK;
+}
 
-  const size_t lut_b = align_up((size_t)Q * M * 256 * 4, 256);
-  const size_t plan_b = align_up((size_t)Q * 4, 256);
-  const size_t probe_b = align_up((size_t)Q * pmax * 4, 256);
-  const size_t scan_b = align_up(scan_ws_bytes(idx->M, Q, lin_rows, topk), 256);
-  const size_t coarse_b = has_lists ? align_up(coarse_ws_bytes(idx, Q, pmax), 256) : 0;
-  const size_t ivf_b = has_lists && topk <= kWaveK ? align_up(ivf_ws_bytes(Q, pmax, topk), 256) : 0;
-  int rc = ensure_ws(idx, lut_b + 2 * plan_b + probe_b + std::max(std::max(scan_b, coarse_b), ivf_b));
-  if (rc) return rc;
-  uint8_t* w = static_cast<uint8_t*>(idx->ws);
-  float* lut = reinterpret_cast<float*>(w); w += lut_b;
-  int* qmode = reinterpret_cast<int*>(w); w += plan_b;
-  int* nprobe_q = reinterpret_cast<int*>(w); w += plan_b;
-  int32_t* probe = reinterpret_cast<int32_t*>(w); w += probe_b;
+static int check_query_args(const rii_index_t* idx, const float* q, int Q, int topk, const int32_t* target_ids,
+                            const int64_t* target_offsets, int64_t max_targets, int64_t L, const int32_t* ids,
+                            const float* dist) {
+  if (!idx || !q || !ids || !dist || Q < 1 || topk < 1 || L < 1 || max_targets < 0) return RII_ERR_INVALID_ARG;
+  if ((target_ids == nullptr) != (target_offsets == nullptr)) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || !m_supported(idx->M) || Q > 65535) return RII_ERR_UNSUPPORTED;
+  if (idx->N < 1) return RII_ERR_INVALID_ARG;
+  return RII_OK;
+}
+
+// Alg. 3 with its scratch at `ws` (p.total bytes).
+static int run_query(const rii_index* idx, const QueryPlan& p, const float* q, int Q, int topk,
+                     const int32_t* target_ids, const int64_t* target_offsets, int64_t L, int32_t* ids, float* dist,
+                     void* ws, hipStream_t st) {
+  const int M = idx->M, K = idx->K;
+  const bool has_lists = K > 0;
+  uint8_t* w = static_cast<uint8_t*>(ws);
+  float* lut = reinterpret_cast<float*>(w); w += p.lut_b;
+  int* qmode = reinterpret_cast<int*>(w); w += p.plan_b;
+  int* nprobe_q = reinterpret_cast<int*>(w); w += p.plan_b;
+  int32_t* probe = reinterpret_cast<int32_t*>(w); w += p.probe_b;
   void* stage_ws = w;
 
   k_build_lut<<<dim3(M, Q), 256, 0, st>>>(idx->d_cb, q, idx->D, M, idx->Ds, lut);
-  k_plan<<<(Q + 255) / 256, 256, 0, st>>>(target_offsets, idx->N, Q, idx->theta, K, L, pmax, qmode, nprobe_q);
+  k_plan<<<(Q + 255) / 256, 256, 0, st>>>(target_offsets, idx->N, Q, idx->theta, K, L, p.pmax, qmode, nprobe_q);
+  int rc = RII_OK;
   // linear-scan branch (mode 0)
   if (target_ids) {
-    rc = launch_scan(idx, idx->d_codes_rows, 0, idx->N, lut, Q, kSubset, target_ids, target_offsets, lin_rows, topk, ids,
-                     dist, topk, qmode, 0, stage_ws, st);
+    rc = launch_scan(idx, idx->d_codes_rows, idx->plane_rows, idx->N, lut, Q, kSubset, target_ids, target_offsets, p.lin_rows, topk,
+                     ids, dist, topk, qmode, 0, stage_ws, st);
   } else if (!has_lists || idx->N < idx->theta) {
     rc = launch_scan(idx, idx->d_codes, idx->plane_codes, idx->N, lut, Q, kLinear, nullptr, nullptr, idx->N, topk, ids, dist, topk,
                      qmode, 0, stage_ws, st);
@@ -586,14 +637,48 @@ int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int
   if (rc) return rc;
   // inverted-index branch (mode 1); the scratch of the scan stage is reused in stream order
   if (has_lists) {
-    rc = coarse_rank(idx, lut, Q, pmax, probe, nullptr, pmax, qmode, 1, stage_ws, st);
+    rc = coarse_rank(idx, lut, Q, p.pmax, probe, nullptr, p.pmax, qmode, 1, stage_ws, st);
     if (rc) return rc;
-    rc = launch_ivf(idx, lut, Q, probe, pmax, pmax, nprobe_q, target_ids, target_offsets, L, topk, ids, dist, qmode,
-                    1, ivf_b ? stage_ws : nullptr, st);
+    rc = launch_ivf(idx, lut, Q, probe, p.pmax, p.pmax, nprobe_q, target_ids, target_offsets, L, topk, ids, dist, qmode,
+                    1, p.ivf_b ? stage_ws : nullptr, st);
     if (rc) return rc;
   }
   RII_HIP(hipGetLastError());
   return RII_OK;
+}
+
+int rii_query(const rii_index_t* idx, const float* q, int Q, int topk, const int32_t* target_ids,
+              const int64_t* target_offsets, int64_t max_targets, int64_t L, int32_t* ids, float* dist,
+              void* stream) {
+  int rc = check_query_args(idx, q, Q, topk, target_ids, target_offsets, max_targets, L, ids, dist);
+  if (rc) return rc;
+  // L >= N asks for all K lists and never cuts the candidates: N says the same, and K * L then
+  // stays far from overflow here and in k_plan
+  if (L > idx->N) L = idx->N;
+  QueryPlan p;
+  rc = plan_query(idx, Q, topk, target_ids != nullptr, max_targets, L, &p);
+  if (rc) return rc;
+  rc = ensure_ws(idx, p.total);
+  if (rc) return rc;
+  return run_query(idx, p, q, Q, topk, target_ids, target_offsets, L, ids, dist, idx->ws, static_cast<hipStream_t>(stream));
+}
+
+int rii_index_reserve_workspace(rii_index_t* idx, int Q, int topk, int64_t max_targets, int nprobe) {
+  if (!idx || Q < 1 || topk < 1 || max_targets < 0 || nprobe < 0) return RII_ERR_INVALID_ARG;
+  if (topk > RII_MAX_TOPK || Q > 65535) return RII_ERR_UNSUPPORTED;
+  const int M = idx->M, K = idx->K;
+  nprobe = std::min(nprobe, std::max(K, 1));
+  // every stage's need, as bounds that grow with Q and topk (so smaller batches fit as well)
+  size_t stage = scan_ws_bound(Q, topk);
+  if (K > 0 && nprobe > 0) {
+    const size_t coarse = nprobe <= RII_MAX_TOPK ? scan_ws_bound(Q, nprobe)
+                                                 : align_up((size_t)Q * K * 4, 256) + align_up((size_t)(Q + 1) * 8, 256);
+    const size_t ivf = kScanArrays * align_up((size_t)Q * 4, 256) + ((size_t)Q + kWantBlocks) * topk * 8 + 256;
+    stage = std::max(stage, std::max(coarse, ivf));
+  }
+  const size_t query = align_up((size_t)Q * M * 256 * 4, 256) + 2 * align_up((size_t)Q * 4, 256) +
+                       align_up((size_t)Q * std::max(nprobe, 1) * 4, 256) + align_up(stage, 256);
+  return ensure_ws(idx, query);
 }
 
 int rii_encode_device(const rii_index_t* idx, const float* x, int64_t n, uint8_t* codes_out, void* stream) {

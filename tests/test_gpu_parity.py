@@ -205,6 +205,117 @@ def test_linear_scan_ties_and_padding(rii, oracle_lib):
         check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
 
 
+@pytest.mark.parametrize("kind", ["uniform", "clustered"])
+def test_linear_scan_plane_fetch_variants(kind, rii, oracle_lib):
+    """M = 32 codes are stored as two 16-byte planes; the one-query scan either fetches second
+    halves on demand or streams both planes, chosen per block or forced by option.  All three
+    settings must give the oracle's result, on codes where nearly every slice stays open half-way
+    (uniform bytes) and on codes where most slices abandon (clustered data), with one, two and
+    three queries per launch (18 blocks per query, ragged last tile)."""
+    from paper_1808_03969_amd import binding
+    N, M = 300001, 32
+    if kind == "uniform":
+        rng = np.random.default_rng(5)
+        cb = rng.normal(size=(M, 256, 2)).astype(np.float32)
+        codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+        q = rng.normal(size=(3, 2 * M)).astype(np.float32)
+    else:
+        x = t2n(synth.mixture(1031, 0, N, 96))
+        q = t2n(synth.mixture(2031, 0, 3, 96))
+        cb = rii.rii_train_codebooks(x[:4000], M, iters=3, seed=9)
+        codes = rii.rii_encode(cb, x)
+    index = rii.Index(cb)
+    index.add(codes)
+    lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+    A = oracle_lib.lut(cb, q)
+    refs = {(i, topk): oracle_lib.linear_scan(A[i], codes, topk) for i in range(3) for topk in (1, 18, 100)}
+    for fetch in (0, 1, 2):
+        index.set_option(binding.RII_OPT_PLANE_FETCH, fetch)
+        for Q in (1, 2, 3):
+            for topk in (1, 18, 100):
+                ids, dist = rii.rii_adc_scan_linear(index, lut[:Q].contiguous(), topk)
+                torch.cuda.synchronize()
+                for i in range(Q):
+                    ref = refs[(i, topk)]
+                    assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), (fetch, Q, topk, i)
+    with pytest.raises(rii.RiiError):
+        index.set_option(binding.RII_OPT_PLANE_FETCH, 3)
+
+
+def test_subset_scan_without_gather_copy(rii, oracle_lib, idx32):
+    """RII_OPT_GATHER_COPY = 0 drops the whole-row copy of M = 32 codes: scans over target
+    identifiers then gather the two halves of a row from the two planes.  Same results, N * M
+    bytes less; the option cannot change once codes are stored."""
+    from paper_1808_03969_amd import binding
+    d = idx32
+    lean = rii.Index(d["cb"])
+    lean.set_option(binding.RII_OPT_GATHER_COPY, 0)
+    lean.add(d["codes"][:40000])
+    lean.add(d["codes"][40000:])                       # grows the array: both planes move
+    with pytest.raises(rii.RiiError):
+        lean.set_option(binding.RII_OPT_GATHER_COPY, 1)
+    full = rii.Index(d["cb"])
+    full.add(d["codes"][:40000])
+    full.add(d["codes"][40000:])
+    assert full.info()["device_bytes"] - lean.info()["device_bytes"] >= d["N"] * 32
+    full.close()
+    assert np.array_equal(lean.get_codes(), d["codes"])
+    lut = rii.rii_build_lut(lean, d["q_dev"])
+    Q = len(d["q"])
+    for sizes, topk in (([5000] * Q, 100), ([d["N"]] * Q, 10), ([1 + 37 * i for i in range(Q)], 129)):
+        tids, toff = synth.subset_batch(91, d["N"], sizes)
+        ids, dist = rii.rii_adc_scan_subset(lean, lut, tids.cuda(), toff.cuda(), max(sizes), topk)
+        torch.cuda.synchronize()
+        for i in range(Q):
+            S = t2n(tids)[t2n(toff)[i]:t2n(toff)[i + 1]]
+            ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], topk, S=S)
+            check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+    lean.set_lists(d["coarse"], d["off"], d["lids"])
+    lean.set_threshold(3000)
+    tids, toff = synth.subset_batch(92, d["N"], [2000, 4000] * (Q // 2))
+    qi, qd = rii.rii_query(lean, d["q_dev"], 50, tids.cuda(), toff.cuda(), 4000, L=2000)
+    torch.cuda.synchronize()
+    for i in range(Q):
+        S = t2n(tids)[t2n(toff)[i]:t2n(toff)[i + 1]]
+        ref = oracle_lib.query(d["cb"], d["q"][i], d["codes"], d["coarse"], d["off"], d["lids"], 50, 2000, 3000, S=S)
+        check_topk(t2n(qi)[i], t2n(qd)[i], ref[0], ref[1])
+
+
+def test_reserve_workspace_then_no_growth(rii, oracle_lib, idx16):
+    """After rii_index_reserve_workspace(Q, topk, ., nprobe) no online call within those limits
+    changes the bytes the handle holds (its scratch is never re-allocated), whatever the batch
+    size; results are the usual ones."""
+    d = idx16
+    index = rii.Index(d["cb"])
+    index.add(d["codes"])
+    index.set_lists(d["coarse"], d["off"], d["lids"])
+    Q, R, K = len(d["q"]), 100, d["K"]
+    index.reserve_workspace(Q, R, max_targets=d["N"], nprobe=K)
+    held = index.info()["device_bytes"]
+    lut = rii.rii_build_lut(index, d["q_dev"])
+    tids, toff = synth.subset_batch(93, d["N"], [7000] * Q)
+    tids, toff = tids.cuda(), toff.cuda()
+    for nq in (1, 2, 3, 4, 5, 8, 17, Q):
+        for topk in (1, 10, R):
+            rii.rii_adc_scan_linear(index, lut[:nq].contiguous(), topk)
+            rii.rii_adc_scan_subset(index, lut[:nq].contiguous(), tids, toff[:nq + 1].contiguous(), 7000, topk)
+            for P in (1, 7, K):
+                probe, _ = rii.rii_coarse_assign(index, lut[:nq].contiguous(), P)
+                rii.rii_adc_scan_ivf(index, lut[:nq].contiguous(), probe, topk)
+            index.set_threshold(5000)
+            rii.rii_query(index, d["q_dev"][:nq].contiguous(), topk, L=d["N"])          # all K lists
+            rii.rii_query(index, d["q_dev"][:nq].contiguous(), topk, tids, toff[:nq + 1].contiguous(), 7000, L=d["N"])
+            index.set_threshold(10 ** 9)
+            rii.rii_query(index, d["q_dev"][:nq].contiguous(), topk)                    # linear branch
+            torch.cuda.synchronize()
+            assert index.info()["device_bytes"] == held, (nq, topk)
+    ids, dist = rii.rii_adc_scan_linear(index, lut, R)
+    torch.cuda.synchronize()
+    for i in range(0, Q, 5):
+        ref = oracle_lib.linear_scan(d["lut_ref"][i], d["codes"], R)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
 @pytest.mark.parametrize("M,Q,topk", [(8, 263, 100), (16, 258, 10)])
 def test_linear_scan_large_batch_in_row_chunks(M, Q, topk, rii, oracle_lib):
     """A batch that takes the several-queries-per-block kernel, over a code array long enough to
@@ -352,6 +463,37 @@ def test_ivf_scan_short_and_empty_lists(M, rii, oracle_lib):
                 S = tids[toff[i]:toff[i + 1]] if use_S else None
                 ref = oracle_lib.inverted_index(d["lut_ref"][i], d["codes"], d["coarse"], d["off"], d["lids"],
                                                 R=20, P=P, S=S, Lcap=L)
+                check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
+@pytest.mark.parametrize("M", [16, 32])
+def test_ivf_scan_nearest_list_empty_and_last(M, rii, oracle_lib):
+    """The nearest probed list of every query is empty and is the last list of the arrays, so its
+    start is one row past the list-ordered codes (N * M a whole number of 2 MB pages here): waves
+    without a next tile must prefetch a real member's row, not that start."""
+    N, K, Q = (1 << 17) if M == 16 else (1 << 16), 33, 5
+    d = make_index(rii, oracle_lib, N=N, D=2 * M, M=M, K=K - 1, seed=12, iters=2, Q=Q)
+    # an extra centre equal to each query's own code would be nearest; one centre serves all
+    # queries here because they are made equal up to a tiny perturbation of the first
+    q = np.repeat(d["q"][:1], Q, axis=0) + np.arange(Q, dtype=np.float32)[:, None] * 1e-3
+    qcode = oracle_lib.encode(d["cb"], q[:1])
+    coarse = np.concatenate([d["coarse"], qcode], axis=0)
+    off = np.concatenate([d["off"], d["off"][-1:]])           # list K-1 empty, start == N
+    d["index"].set_lists(coarse, off, d["lids"])
+    A = oracle_lib.lut(d["cb"], q)
+    lut = rii.rii_build_lut(d["index"], torch.from_numpy(q).cuda())
+    tids, toff = synth.subset_batch(82, N, [N // 3] * Q)
+    for P in (1, 2, 9, K):
+        probe, _ = rii.rii_coarse_assign(d["index"], lut, P)
+        assert np.all(t2n(probe)[:, 0] == K - 1)
+        for use_S, L in ((False, 0), (True, 0), (False, 700), (True, 50)):
+            ids, dist = rii.rii_adc_scan_ivf(d["index"], lut, probe, 10,
+                                             target_ids=tids.cuda() if use_S else None,
+                                             target_offsets=toff.cuda() if use_S else None, L=L)
+            torch.cuda.synchronize()
+            for i in range(Q):
+                S = t2n(tids)[t2n(toff)[i]:t2n(toff)[i + 1]] if use_S else None
+                ref = oracle_lib.inverted_index(A[i], d["codes"], coarse, off, d["lids"], R=10, P=P, S=S, Lcap=L)
                 check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
 
 
