@@ -19,8 +19,9 @@ rate of bytes the kernel really moved (`traffic`, from the tallies the kernel ke
 launches: first plane streamed, second-plane lines fetched on demand or streamed) against the
 8 TB/s peak, so it cannot exceed 1; the method's own M bytes per code are reported beside it
 (`algorithmic_bytes_per_launch`, `algorithmic_gbs`, `moved_over_algorithmic`).
-`roofline_no_pruning` -- the same kernel over N independent uniform code bytes, where half-way
-abandoning saves nothing and the kernel streams every byte: moved = algorithmic.
+`roofline_no_pruning` -- the same kernel over N independent uniform code bytes, where nearly every
+128-byte line of second halves has a row that is still open half-way, so the kernel ends up
+fetching (nearly) every byte: moved = algorithmic.
 `roofline_batched` -- the batched launch of the timed steps (k_scan_w4: four queries share each
 code byte, so the bound is the LDS look-up rate; `achieved` counts the look-ups the kernel really
 made -- it abandons part of them -- and `peak` is the best rate the library's look-up-only kernel
@@ -80,8 +81,6 @@ def main():
     ap.add_argument("--nprobe", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform-leg", action="store_true", help="skip roofline_no_pruning (the scan of uniform random codes)")
-    ap.add_argument("--plane-variants", action="store_true",
-                    help="also time the one-query scan with the second plane forced on demand / forced streamed")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain streaming kernel of known size (1 GiB read + 1 GiB written) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -170,11 +169,9 @@ def main():
     scored = Q * N + Q * S + (probed + probed_query + 2 * Q * K if K else 0)
     value = scored / (ms_per_step * 1e-3)
 
-    def one_query_leg(idx, n_rows, lut1, what, launches=12, plane_fetch=None):
+    def one_query_leg(idx, n_rows, lut1, what, launches=12):
         """One query per launch over `idx`: launch time from the events around the kernel, bytes
         moved from the kernel's own tallies of the same launches."""
-        if plane_fetch is not None:
-            idx.set_option(binding.RII_OPT_PLANE_FETCH, plane_fetch)
         rii.rii_index_set_scan_events(idx, ev.start.value, ev.stop.value)
         for i in range(2):                                   # warm-up (also sizes the scratch)
             rii.rii_adc_scan_linear(idx, lut1[i % len(lut1):i % len(lut1) + 1], R)
@@ -187,14 +184,12 @@ def main():
             ms.append(ev.elapsed_ms())
         c = binding.rii_index_read_scan_counters(idx)
         rii.rii_index_set_scan_events(idx, None, None)
-        if plane_fetch is not None:
-            idx.set_option(binding.RII_OPT_PLANE_FETCH, 0)
         launch_ms = float(np.mean(ms))
         algorithmic = float(n_rows) * M                      # M bytes per code and query pass
         if M == 32:
             # two planes of 16 bytes per row: the first is streamed whole; of the second, the
-            # 128-byte lines fetched on demand plus the 256-row wave-tiles streamed along
-            moved = n_rows * 16.0 + (128.0 * c[2] + 256 * 16.0 * c[3]) / launches
+            # 128-byte lines the kernel asked for
+            moved = n_rows * 16.0 + 128.0 * c[2] / launches
         else:
             moved = algorithmic
         moved = min(moved, algorithmic)                      # (rows re-read at block seams are cache hits)
@@ -202,13 +197,12 @@ def main():
         return {
             "bound": "hbm", "kernel": f"k_scan_w<{M},linear>, one query per launch, {what}",
             "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-            "traffic": moved, "traffic_source": "kernel tallies of the timed launches (second-plane lines and tiles)"
+            "traffic": moved, "traffic_source": "kernel tallies of the timed launches (first plane streamed + second-plane lines fetched)"
                                                if M == 32 else "every code byte is read once",
             "launch_ms": round(launch_ms, 4), "launch_ms_min_max": [round(min(ms), 4), round(max(ms), 4)],
             "algorithmic_bytes_per_launch": algorithmic,
             "algorithmic_gbs": round(algorithmic / (launch_ms * 1e-3) / 1e9, 1),
             "moved_over_algorithmic": round(moved / algorithmic, 4),
-            "blocks_streaming_both_planes": int(c[4] // launches), "blocks_fetching_on_demand": int(c[5] // launches),
             "codes_per_s": round(n_rows / (launch_ms * 1e-3), 1),
         }
 
@@ -230,14 +224,7 @@ def main():
         torch.cuda.synchronize()
         log(f"{N} uniform random codes stored in {time.time() - t0:.1f}s")
         no_pruning = one_query_leg(uni, N, lut, "independent uniform code bytes")
-        if args.plane_variants and M == 32:
-            no_pruning["forced_on_demand_ms"] = one_query_leg(uni, N, lut, "", plane_fetch=1)["launch_ms"]
-            no_pruning["forced_both_planes_ms"] = one_query_leg(uni, N, lut, "", plane_fetch=2)["launch_ms"]
         uni.close()
-    if args.plane_variants and M == 32:
-        roofline["forced_on_demand_ms"] = one_query_leg(index, N, lut, "", plane_fetch=1)["launch_ms"]
-        both = one_query_leg(index, N, lut, "", plane_fetch=2)
-        roofline["forced_both_planes_ms"], roofline["forced_both_planes_frac"] = both["launch_ms"], both["frac"]
 
     # The batched launch: look-ups, not bytes, are what bounds it.
     batched = None

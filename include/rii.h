@@ -125,17 +125,12 @@ int rii_index_reconfigure(rii_index_t* index, int K, int iters, uint64_t seed);
 int rii_index_set_threshold(rii_index_t* index, int64_t theta);
 
 /* Options of a handle (rii_index_set_option).  None of them changes any result.
- *   RII_OPT_PLANE_FETCH   how the one-query whole-database scan reads an M = 32 code array, which is
- *                         stored as two planes of 16 bytes per row: 0 (default) every block decides
- *                         from its first rows whether to stream both planes or to fetch second
- *                         halves only for rows still within the bound after 16 look-ups; 1 always
- *                         on demand; 2 always both planes.
  *   RII_OPT_GATHER_COPY   M = 32 only: 1 (default) keeps the codes a second time as whole 32-byte
  *                         rows, which is what scans over target identifiers gather from (one memory
  *                         line per row); 0 drops that copy (N M bytes less; such scans then gather
- *                         the two halves of a row from the two planes).  Must be set before the
- *                         first rii_index_add. */
-enum { RII_OPT_PLANE_FETCH = 1, RII_OPT_GATHER_COPY = 2 };
+ *                         the two halves of a row from the two 16-byte planes the sequential scans
+ *                         read).  Must be set before the first rii_index_add. */
+enum { RII_OPT_GATHER_COPY = 2 };
 int rii_index_set_option(rii_index_t* index, int option, int64_t value);
 
 /* Size the handle's scratch once, so that no later online call has to grow it (growing it frees and

@@ -27,10 +27,9 @@ int rii_index_set_scan_events(rii_index_t* index, void* start_event, void* stop_
  *   [1] batched scan: slices abandoned half-way (only M/2 look-ups each were made)
  *   one-query scan of an M = 32 array (two planes of 16 bytes per row; the first plane is always
  *   streamed, N x 16 bytes per pass):
- *   [2] 128-byte memory lines of the second plane fetched on demand
- *   [3] wave-tiles (256 rows) whose second plane was streamed along with the first
- *   [4] blocks that streamed both planes, [5] blocks that fetched second halves on demand
- *   [6], [7] unused (zero). */
+ *   [2] 128-byte memory lines of the second plane it fetched (a row's second half is asked for
+ *       only when its first 16 look-ups leave it within the bound)
+ *   [3] .. [7] unused (zero). */
 int rii_index_read_scan_counters(rii_index_t* index, uint64_t* counters_out);
 
 /* Launch shape rii_adc_scan_linear uses for a batch of Q queries on this index (so that a

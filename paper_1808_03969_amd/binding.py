@@ -21,7 +21,7 @@ _lib = None
 
 RII_MEM_HOST, RII_MEM_DEVICE = 0, 1
 RII_MAX_TOPK, RII_MAX_SORT = 1024, 16384
-RII_OPT_PLANE_FETCH, RII_OPT_GATHER_COPY = 1, 2
+RII_OPT_GATHER_COPY = 2
 RII_SCAN_COUNTERS = 8
 
 

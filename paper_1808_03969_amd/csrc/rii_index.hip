@@ -324,10 +324,6 @@ int rii_index_read_scan_counters(rii_index_t* idx, uint64_t* counters_out) {
 int rii_index_set_option(rii_index_t* idx, int option, int64_t value) {
   if (!idx) return RII_ERR_INVALID_ARG;
   switch (option) {
-    case RII_OPT_PLANE_FETCH:
-      if (value < 0 || value > 2) return RII_ERR_INVALID_ARG;
-      idx->plane_fetch = (int)value;
-      return RII_OK;
     case RII_OPT_GATHER_COPY:
       if (value != 0 && value != 1) return RII_ERR_INVALID_ARG;
       if (idx->cap > 0 && (value != 0) != idx->keep_rows_copy) return RII_ERR_INVALID_ARG;  // layout is fixed once codes are stored

@@ -30,7 +30,6 @@ struct rii_index {
   int64_t plane_codes = 0, plane_list = 0, plane_coarse = 0;
   int64_t plane_rows = 0;         // plane distance of d_codes_rows: 0 (whole rows) unless it is d_codes itself
   bool keep_rows_copy = true;     // M = 32: keep the whole-row copy for gathered scans (RII_OPT_GATHER_COPY)
-  int plane_fetch = 0;            // RII_OPT_PLANE_FETCH: how the one-query scan reads the second plane
   uint8_t* d_codes = nullptr;     // [cap][M] codes in identifier order (the linear array), stored form
   uint8_t* d_codes_rows = nullptr;  // [cap][M] the same rows, rotated, never split (what the subset scan gathers from)
   uint8_t* d_coarse = nullptr;    // [K][M] coarse centres (PQ codes), plain

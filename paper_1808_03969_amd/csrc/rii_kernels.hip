@@ -64,6 +64,8 @@ int ensure_ws(const rii_index* idx, size_t bytes) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+constexpr bool kUsePool = false;  // (the shared row pool of the one-query scan: measured without gain so far)
+
 bool m_supported(int M) { return M >= 4 && M <= RII_MAX_M && M % 4 == 0; }
 
 // Per (device, kernel): the dynamic LDS size already granted with hipFuncSetAttribute, and whether
@@ -166,7 +168,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   int64_t nchunks, chunk_rows;
   scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
 
-  // workspace: [tau Q][candidate count Q][prepass counter Q][blocks done Q] u32, then
+  // workspace: [tau Q][candidate count Q][prepass counter Q][blocks done Q][pool units taken Q] u32, then
   // [candidates], then [prepass minima]
   // (the four arrays start 256-byte aligned so that, for a single query, the much-read bound
   // does not share a cache line with the counters the blocks update)
@@ -176,6 +178,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   uint32_t* cand_cnt = tau + cstride;
   uint32_t* pre_counter = tau + 2 * cstride;
   uint32_t* done_cnt = tau + 3 * cstride;
+  uint32_t* pool_cnt = tau + 4 * cstride;
   uint64_t* partial = reinterpret_cast<uint64_t*>(base + kScanArrays * cstride * 4);
 
   ScanArgs a{};
@@ -188,14 +191,13 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   a.nq = Q;
   // [prepass minima] follow the candidates
   uint32_t* minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * a.cand_cap);
-  k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
   a.done_cnt = done_cnt; a.ids = ids; a.dist = dist; a.out_stride = out_stride;
+  a.pool_lo = INT64_MAX; a.pool_cnt = pool_cnt;
   a.qmode = qmode; a.want_mode = want_mode;
   dim3 grid((unsigned)nchunks, (unsigned)Q);
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   const bool timed = mode == kLinear && idx->ev_start && idx->ev_stop && codes == idx->d_codes;
   a.counters = timed ? idx->d_scan_counters : nullptr;
-  a.plane_fetch = idx->plane_fetch;
   if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
   if (topk <= kWaveK) {
     // When a query's rows are split over several blocks, a short first pass over the leading
@@ -217,6 +219,17 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
                              (int64_t)Q * nchunks <= kWantBlocks;
     const bool prepass = nchunks > 1 && !seed_inside;
     a.seed_inside = seed_inside ? 1 : 0;
+    // Whole-database scan by several one-query blocks per query: the blocks' fixed shares cover
+    // seven eighths of the rows, the rest is a pool any wave takes units from when its block's
+    // share is used up -- a block that streams slower than the others ends up with fewer rows.
+    if (kUsePool && mode == kLinear && rot_m(M) && !batched && nchunks > 1) {
+      const int64_t fixed = (max_rows - max_rows / 8) / nchunks / tile_rows * tile_rows;
+      if (fixed >= kMinTiles * tile_rows) {
+        a.chunk_rows = fixed;
+        a.pool_lo = fixed * nchunks;
+      }
+    }
+    k_init_scan<<<(std::max(Q, 256) + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, minima, seed_inside ? Q * (int)nchunks : 0);
     a.minima = minima;
     a.counter = pre_counter;
     ScanArgs pre = a;
@@ -294,6 +307,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
                       k_scan_w<MT, kSubset><<<grid, kScanThreads, ldsw, st>>>(a); });
     }
   } else {
+  k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, nullptr, 0);
   const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
   if (mode == kLinear) {
     DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kLinear>, lds); if (rc) return rc;
@@ -529,7 +543,7 @@ static int launch_ivf(const rii_index* idx, const float* lut, int Q, const int32
     a.tau_g = tau; a.cand_cnt = tau + cstride; a.done_cnt = tau + 3 * cstride;
     a.cand = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(ws) + kScanArrays * cstride * 4);
     a.cand_cap = (int64_t)split * topk;
-    k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride);
+    k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, nullptr, 0);
     const size_t ldsw = ivf_w_lds(M, nprobe);
     dim3 grid((unsigned)split, (unsigned)Q);
     DISPATCH_M(M, { int rc = set_lds0(k_ivf_w<MT>, ldsw); if (rc) return rc;

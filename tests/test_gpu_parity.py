@@ -206,13 +206,12 @@ def test_linear_scan_ties_and_padding(rii, oracle_lib):
 
 
 @pytest.mark.parametrize("kind", ["uniform", "clustered"])
-def test_linear_scan_plane_fetch_variants(kind, rii, oracle_lib):
-    """M = 32 codes are stored as two 16-byte planes; the one-query scan either fetches second
-    halves on demand or streams both planes, chosen per block or forced by option.  All three
-    settings must give the oracle's result, on codes where nearly every slice stays open half-way
-    (uniform bytes) and on codes where most slices abandon (clustered data), with one, two and
-    three queries per launch (18 blocks per query, ragged last tile)."""
-    from paper_1808_03969_amd import binding
+def test_linear_scan_two_planes_pool_and_seeding(kind, rii, oracle_lib):
+    """M = 32 codes are stored as two 16-byte planes and the one-query scan fetches second halves
+    on demand: on codes where nearly every slice stays open half-way (uniform bytes) and on codes
+    where most slices abandon (clustered data).  N is large enough for the blocks' fixed shares
+    plus the shared pool of row units (18 blocks per query), with a ragged last tile; topk on both
+    sides of the switch between bound seeding inside the kernel and the separate pass."""
     N, M = 300001, 32
     if kind == "uniform":
         rng = np.random.default_rng(5)
@@ -228,18 +227,14 @@ def test_linear_scan_plane_fetch_variants(kind, rii, oracle_lib):
     index.add(codes)
     lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
     A = oracle_lib.lut(cb, q)
-    refs = {(i, topk): oracle_lib.linear_scan(A[i], codes, topk) for i in range(3) for topk in (1, 18, 100)}
-    for fetch in (0, 1, 2):
-        index.set_option(binding.RII_OPT_PLANE_FETCH, fetch)
+    for topk in (1, 18, 19, 100):
+        refs = [oracle_lib.linear_scan(A[i], codes, topk) for i in range(3)]
         for Q in (1, 2, 3):
-            for topk in (1, 18, 100):
+            for rep in range(2):
                 ids, dist = rii.rii_adc_scan_linear(index, lut[:Q].contiguous(), topk)
                 torch.cuda.synchronize()
                 for i in range(Q):
-                    ref = refs[(i, topk)]
-                    assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), (fetch, Q, topk, i)
-    with pytest.raises(rii.RiiError):
-        index.set_option(binding.RII_OPT_PLANE_FETCH, 3)
+                    assert np.array_equal(t2n(ids)[i], refs[i][0]) and np.array_equal(t2n(dist)[i], refs[i][1]), (Q, topk, i, rep)
 
 
 def test_subset_scan_without_gather_copy(rii, oracle_lib, idx32):
