@@ -239,6 +239,24 @@ int rii_query(const rii_index_t* index, const float* q, int Q, int topk, const i
               const int64_t* target_offsets, int64_t max_targets, int64_t L, int32_t* ids, float* dist,
               void* stream);
 
+/* rii_query for callers that cannot allocate device memory while they search: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results and same kernels as rii_query; the scratch (distance tables, per-query plan, probed
+ * lists, candidate lists, bounds and counters) is not the handle's but one array of
+ * RII_NOALLOC_SCRATCH_BYTES in the library's own device image, which every GPU the library runs
+ * on holds until the process ends.  The call makes no hipMalloc / hipFree and no other allocating
+ * runtime call.
+ *   Returns RII_ERR_UNSUPPORTED when the batch needs more scratch than the array holds (the need
+ *   grows with Q (M + topk) and, for the inverted index, Q ceil(K L / |S|)); RII_ERR_INVALID_ARG
+ *   when the current device is not the handle's.
+ *   All calls on one GPU share that array, which keeps the last call's contents (the kernels
+ *   clear what has to start from zero): two calls that overlap on one GPU -- different streams,
+ *   different handles, different threads -- race.  Issue them on one stream. */
+#define RII_NOALLOC_SCRATCH_BYTES (64 * 1024 * 1024)
+int rii_query_noalloc(const rii_index_t* index, const float* q, int Q, int topk, const int32_t* target_ids,
+                      const int64_t* target_offsets, int64_t max_targets, int64_t L, int32_t* ids, float* dist,
+                      void* stream);
+
 /* ------------------------------------------------------------------ device, offline ---- */
 
 /* Eq. (1) on the GPU, bit-identical to rii_encode.

@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     RiiError, Index, load_library, library_path,
     rii_train_codebooks, rii_encode, rii_build_lut, rii_coarse_assign, rii_adc_scan_linear,
     rii_adc_scan_subset, rii_adc_scan_ivf, rii_topk, rii_query, rii_encode_device, rii_assign,
-    rii_index_set_scan_events, rii_rotate, rii_check_target_ids,
+    rii_index_set_scan_events, rii_rotate, rii_check_target_ids, rii_query_noalloc,
 )

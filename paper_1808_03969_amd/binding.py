@@ -301,6 +301,21 @@ def rii_query(index: Index, q: torch.Tensor, topk: int, target_ids: torch.Tensor
     return ids, dist
 
 
+def rii_query_noalloc(index: Index, q: torch.Tensor, topk: int, target_ids: torch.Tensor | None = None,
+                      target_offsets: torch.Tensor | None = None, max_targets: int = 0, L: int = 1, out=None):
+    """rii_query on the library's static scratch array; `out` = (ids, dist) must be given when the
+    caller may not allocate (otherwise torch allocates the two result tensors)."""
+    Q = q.shape[0]
+    if q.dim() != 2 or q.shape[1] != index.D:
+        raise ValueError("q must be [Q][D]")
+    ids, dist = out if out is not None else _out(Q, max(topk, 1), q.device)
+    _check(load_library().rii_query_noalloc(index.handle, _dp(q, torch.float32), Q, topk, _dp(target_ids, torch.int32),
+                                            _dp(target_offsets, torch.int64), i64(max_targets), i64(L),
+                                            _dp(ids, torch.int32), _dp(dist, torch.float32), _stream()),
+           "rii_query_noalloc")
+    return ids, dist
+
+
 # ------------------------------------------------------------------ device, offline
 def rii_encode_device(index: Index, x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
     n = x.shape[0]

@@ -695,6 +695,49 @@ int rii_index_reserve_workspace(rii_index_t* idx, int Q, int topk, int64_t max_t
   return ensure_ws(idx, query);
 }
 
+// ---- the query procedure without any allocation ---------------------------------------------
+// Scratch of rii_query_noalloc: one array per GPU, in the library's own device image.  In host
+// code the array's name only stands for it; its device address is asked for once per device
+// (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[RII_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static int scratch_of_current_device(void** out) {
+  int dev = -1;
+  RII_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return RII_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    RII_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return RII_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return RII_OK;
+}
+
+int rii_query_noalloc(const rii_index_t* idx, const float* q, int Q, int topk, const int32_t* target_ids,
+                      const int64_t* target_offsets, int64_t max_targets, int64_t L, int32_t* ids, float* dist,
+                      void* stream) {
+  int rc = check_query_args(idx, q, Q, topk, target_ids, target_offsets, max_targets, L, ids, dist);
+  if (rc) return rc;
+  if (L > idx->N) L = idx->N;
+  int dev = -1;
+  RII_HIP(hipGetDevice(&dev));
+  if (dev != idx->device) return RII_ERR_INVALID_ARG;  // the handle's arrays live on another GPU
+  QueryPlan p;
+  rc = plan_query(idx, Q, topk, target_ids != nullptr, max_targets, L, &p);
+  if (rc) return rc;
+  if (p.total > (size_t)RII_NOALLOC_SCRATCH_BYTES) return RII_ERR_UNSUPPORTED;  // beyond the static scratch
+  void* ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc) return rc;
+  return run_query(idx, p, q, Q, topk, target_ids, target_offsets, L, ids, dist, ws, static_cast<hipStream_t>(stream));
+}
+
 int rii_encode_device(const rii_index_t* idx, const float* x, int64_t n, uint8_t* codes_out, void* stream) {
   if (!idx || n < 0 || (n > 0 && (!x || !codes_out))) return RII_ERR_INVALID_ARG;
   if (n == 0) return RII_OK;
