@@ -64,7 +64,6 @@ int ensure_ws(const rii_index* idx, size_t bytes) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-constexpr bool kUsePool = false;  // (the shared row pool of the one-query scan: measured without gain so far)
 
 bool m_supported(int M) { return M >= 4 && M <= RII_MAX_M && M % 4 == 0; }
 
@@ -168,7 +167,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   int64_t nchunks, chunk_rows;
   scan_chunks(Q, max_rows, &nchunks, &chunk_rows);
 
-  // workspace: [tau Q][candidate count Q][prepass counter Q][blocks done Q][pool units taken Q] u32, then
+  // workspace: [tau Q][candidate count Q][prepass counter Q][blocks done Q] u32, then
   // [candidates], then [prepass minima]
   // (the four arrays start 256-byte aligned so that, for a single query, the much-read bound
   // does not share a cache line with the counters the blocks update)
@@ -178,7 +177,6 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   uint32_t* cand_cnt = tau + cstride;
   uint32_t* pre_counter = tau + 2 * cstride;
   uint32_t* done_cnt = tau + 3 * cstride;
-  uint32_t* pool_cnt = tau + 4 * cstride;
   uint64_t* partial = reinterpret_cast<uint64_t*>(base + kScanArrays * cstride * 4);
 
   ScanArgs a{};
@@ -192,13 +190,11 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   // [prepass minima] follow the candidates
   uint32_t* minima = reinterpret_cast<uint32_t*>(partial + (size_t)Q * a.cand_cap);
   a.done_cnt = done_cnt; a.ids = ids; a.dist = dist; a.out_stride = out_stride;
-  a.pool_lo = INT64_MAX; a.pool_cnt = pool_cnt;
   a.qmode = qmode; a.want_mode = want_mode;
   dim3 grid((unsigned)nchunks, (unsigned)Q);
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   const bool timed = mode == kLinear && idx->ev_start && idx->ev_stop && codes == idx->d_codes;
   a.counters = timed ? idx->d_scan_counters : nullptr;
-  if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
   if (topk <= kWaveK) {
     // When a query's rows are split over several blocks, a short first pass over the leading
     // rows seeds the shared bound, so that the main pass starts with few candidates.
@@ -219,17 +215,8 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
                              (int64_t)Q * nchunks <= kWantBlocks;
     const bool prepass = nchunks > 1 && !seed_inside;
     a.seed_inside = seed_inside ? 1 : 0;
-    // Whole-database scan by several one-query blocks per query: the blocks' fixed shares cover
-    // seven eighths of the rows, the rest is a pool any wave takes units from when its block's
-    // share is used up -- a block that streams slower than the others ends up with fewer rows.
-    if (kUsePool && mode == kLinear && rot_m(M) && !batched && nchunks > 1) {
-      const int64_t fixed = (max_rows - max_rows / 8) / nchunks / tile_rows * tile_rows;
-      if (fixed >= kMinTiles * tile_rows) {
-        a.chunk_rows = fixed;
-        a.pool_lo = fixed * nchunks;
-      }
-    }
     k_init_scan<<<(std::max(Q, 256) + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, minima, seed_inside ? Q * (int)nchunks : 0);
+    if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
     a.minima = minima;
     a.counter = pre_counter;
     ScanArgs pre = a;
@@ -308,6 +295,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
     }
   } else {
   k_init_scan<<<(Q + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, nullptr, 0);
+  if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
   const size_t lds = (size_t)M * 1024 + (size_t)kSelCap * 8;
   if (mode == kLinear) {
     DISPATCH_M(M, { int rc = set_lds(k_scan<MT, kLinear>, lds); if (rc) return rc;
@@ -329,9 +317,14 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
 }
 
 // Minima of the bound-seeding pass: it only runs when the rows of a query are cut into chunks,
-// which launches of kSeedMaxQ or more queries never do.
+// which launches of kSeedMaxQ or more queries never do, and with four or more queries it has
+// at most kPrepassBlocks / 2 blocks per query (see launch_scan).
 constexpr int kSeedMaxQ = 2048;
-size_t minima_bytes(int Q) { return (size_t)std::min(Q, kSeedMaxQ) * kPrepassBlocks * (kScanThreads / 64) * 4; }
+static_assert(kSeedMaxQ >= 8 * kWantBlocks, "batches that are cut into row chunks have fewer than 2 * kWantBlocks groups of four");
+size_t minima_bytes(int Q) {
+  const size_t blocks = Q < 4 ? kPrepassBlocks : kPrepassBlocks / 2;
+  return (size_t)std::min(Q, kSeedMaxQ) * blocks * (kScanThreads / 64) * 4;
+}
 
 size_t scan_ws_bytes(int M, int Q, int64_t max_rows, int topk) {
   int64_t nchunks, chunk_rows;
@@ -347,7 +340,8 @@ size_t scan_ws_bytes(int M, int Q, int64_t max_rows, int topk) {
 // below Q + 4 kBatchWantBlocks + kWantBlocks whatever the launch shape is).
 size_t scan_ws_bound(int Q, int topk) {
   return kScanArrays * align_up((size_t)Q * 4, 256) +
-         ((size_t)Q + 4 * kBatchWantBlocks + kWantBlocks + 8) * topk * 8 + minima_bytes(Q) + 256;
+         ((size_t)Q + 4 * kBatchWantBlocks + kWantBlocks + 8) * topk * 8 +
+         std::max(minima_bytes(Q), minima_bytes(std::min(Q, 3))) + 256;
 }
 
 }  // namespace

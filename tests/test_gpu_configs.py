@@ -10,6 +10,9 @@ three levels:
   * index parity on samples: Eq. (1) codes and a(n) of sampled rows equal the oracle's, the
     posting lists partition the identifiers in ascending order.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -38,6 +41,14 @@ def build(rii, name, **kw):
     if cfg.K:
         w["coarse"], w["off"], w["lids"], w["assign"] = w["index"].get_lists()
     return w
+
+
+def oracle_many(fn, items):
+    """fn(item) for every item on the host's threads (the oracle's routines are single-threaded
+    and release the interpreter lock while they run); results in the order of `items`."""
+    workers = max(1, min(len(items), int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)))
+    with ThreadPoolExecutor(workers) as pool:
+        return list(pool.map(fn, items))
 
 
 def certify(oracle, A, codes, ids, dist, pool=None):
@@ -177,18 +188,24 @@ def test_c4_deep_shaped_with_additions(rii, oracle_lib):
     ids, dist = t2n(ids), t2n(dist)
     for i in range(0, Q, 20):
         certify(oracle_lib, A[i], w["codes"], ids[i], dist[i])
-    for i in range(0, Q, 500):                                   # 20 queries through Alg. 1 (1.6e8 look-ups each)
-        ref = oracle_lib.linear_scan(A[i], w["codes"], R)
+    sample = list(range(0, Q, 150))                              # 67 queries through Alg. 1 (1.6e8 look-ups each)
+    for i, ref in zip(sample, oracle_many(lambda i: oracle_lib.linear_scan(A[i], w["codes"], R), sample)):
         check_topk(ids[i], dist[i], ref[0], ref[1])
+        if i % 600 == 0:                                         # the one-query-per-launch shape on 17 of them
+            one = rii.rii_adc_scan_linear(index, lut[i:i + 1], R)
+            torch.cuda.synchronize()
+            assert np.array_equal(t2n(one[0])[0], ref[0]) and np.array_equal(t2n(one[1])[0], ref[1])
 
     def check_ivf(codes, coarse, off, lids, nprobes, every):
         for nprobe in nprobes:
             probe, _ = rii.rii_coarse_assign(index, lut, nprobe)
             iv = rii.rii_adc_scan_ivf(index, lut, probe, R)
             torch.cuda.synchronize()
-            for i in range(0, Q, every):
-                ref = oracle_lib.inverted_index(A[i], codes, coarse, off, lids, R, nprobe)
-                check_topk(t2n(iv[0])[i], t2n(iv[1])[i], ref[0], ref[1])
+            iv_i, iv_d = t2n(iv[0]), t2n(iv[1])
+            sample = list(range(0, Q, every))
+            refs = oracle_many(lambda i: oracle_lib.inverted_index(A[i], codes, coarse, off, lids, R, nprobe), sample)
+            for i, ref in zip(sample, refs):
+                check_topk(iv_i[i], iv_d[i], ref[0], ref[1])
 
     check_ivf(w["codes"], w["coarse"], w["off"], w["lids"], (16, 64), 100)
     # 20 % new vectors from shifted components, encoded with the old code books (Sec. 5.4 shape)
@@ -205,18 +222,17 @@ def test_c4_deep_shaped_with_additions(rii, oracle_lib):
     assert np.array_equal(oracle_lib.assign(T, codes2[rows], coarse2), a2[rows])
     off_ref, lids_ref = oracle_lib.build_lists(a2, cfg.K)
     assert np.array_equal(off2, off_ref) and np.array_equal(lids2, lids_ref)
-    check_ivf(codes2, coarse2, off2, lids2, (16,), 250)          # before list re-assignment
+    check_ivf(codes2, coarse2, off2, lids2, (16,), 150)          # before list re-assignment (67 queries)
     lin2 = rii.rii_adc_scan_linear(index, lut[:64].contiguous(), R)
     torch.cuda.synchronize()
-    for i in range(0, 64, 16):
-        ref = oracle_lib.linear_scan(A[i], codes2, R)
+    for i, ref in enumerate(oracle_many(lambda i: oracle_lib.linear_scan(A[i], codes2, R), list(range(64)))):
         check_topk(t2n(lin2[0])[i], t2n(lin2[1])[i], ref[0], ref[1])
     index.reconfigure(cfg.K, iters=2, seed=4004)                 # Alg. 4
     coarse3, off3, lids3, a3 = index.get_lists()
     assert np.array_equal(oracle_lib.assign(T, codes2[rows], coarse3), a3[rows])
     off_ref, lids_ref = oracle_lib.build_lists(a3, cfg.K)
     assert np.array_equal(off3, off_ref) and np.array_equal(lids3, lids_ref)
-    check_ivf(codes2, coarse3, off3, lids3, (16, 64), 250)       # after list re-assignment
+    check_ivf(codes2, coarse3, off3, lids3, (16, 64), 150)       # after list re-assignment
 
 
 def test_c5_billion_scale_shard(rii, oracle_lib):
@@ -230,19 +246,26 @@ def test_c5_billion_scale_shard(rii, oracle_lib):
     ids, dist = t2n(ids), t2n(dist)
     for i in range(0, Q, 10):
         certify(oracle_lib, A[i], w["codes"], ids[i], dist[i])
-    sample = (0, 3333, 9999)
-    for i in sample:                                             # 3.2e9 look-ups per query
-        ref = oracle_lib.linear_scan(A[i], w["codes"], R)
+    # 66 queries through Alg. 1 (3.2e9 look-ups each), spread over the batch so that they come from
+    # different four-query groups and include the last one; each also as a one-query launch
+    # (255 blocks with the bound seeded inside the kernel)
+    sample = sorted(set(range(0, Q, 157)) | {3333, 9999})
+    for i, ref in zip(sample, oracle_many(lambda i: oracle_lib.linear_scan(A[i], w["codes"], R), sample)):
         check_topk(ids[i], dist[i], ref[0], ref[1])
-        one = rii.rii_adc_scan_linear(index, lut[i:i + 1], R)    # one query per launch (2,035 blocks)
+        one = rii.rii_adc_scan_linear(index, lut[i:i + 1], R)
         torch.cuda.synchronize()
         assert np.array_equal(t2n(one[0])[0], ref[0]) and np.array_equal(t2n(one[1])[0], ref[1])
+    few = rii.rii_adc_scan_linear(index, lut[40:43].contiguous(), R)   # three queries: 85 blocks each, separate seeding pass
+    torch.cuda.synchronize()
+    assert np.array_equal(t2n(few[0]), ids[40:43]) and np.array_equal(t2n(few[1]), dist[40:43])
     probe, _ = rii.rii_coarse_assign(index, lut, 64)
     iv = rii.rii_adc_scan_ivf(index, lut, probe, R)
     torch.cuda.synchronize()
-    for i in range(0, Q, 200):
-        ref = oracle_lib.inverted_index(A[i], w["codes"], w["coarse"], w["off"], w["lids"], R, 64)
-        check_topk(t2n(iv[0])[i], t2n(iv[1])[i], ref[0], ref[1])
+    iv_i, iv_d = t2n(iv[0]), t2n(iv[1])
+    sample = list(range(0, Q, 150))                              # 67 queries through Alg. 2
+    refs = oracle_many(lambda i: oracle_lib.inverted_index(A[i], w["codes"], w["coarse"], w["off"], w["lids"], R, 64), sample)
+    for i, ref in zip(sample, refs):
+        check_topk(iv_i[i], iv_d[i], ref[0], ref[1])
     Qs, S = 256, 1_000_000
     tids, toff = synth.subset_batch(5005, N, [S] * Qs, "cuda")
     sub = rii.rii_adc_scan_subset(index, lut[:Qs].contiguous(), tids, toff, S, R)
@@ -250,11 +273,14 @@ def test_c5_billion_scale_shard(rii, oracle_lib):
     qry = rii.rii_query(index, w["q"][:Qs].contiguous(), R, L=L)
     torch.cuda.synchronize()
     th, to = t2n(tids), t2n(toff)
-    for i in range(0, Qs, 8):
+    sub_i, sub_d, qry_i, qry_d = t2n(sub[0]), t2n(sub[1]), t2n(qry[0]), t2n(qry[1])
+    sample = list(range(0, Qs, 4))                               # 64 queries each through Alg. 1 with S and Alg. 3
+    refs_sub = oracle_many(lambda i: oracle_lib.linear_scan(A[i], w["codes"], R, S=th[to[i]:to[i + 1]]), sample)
+    refs_qry = oracle_many(lambda i: oracle_lib.query(w["cb"], w["q_host"][i], w["codes"], w["coarse"], w["off"], w["lids"],
+                                                      R, L, 0), sample)
+    for i, rs, rq in zip(sample, refs_sub, refs_qry):
         Sq = th[to[i]:to[i + 1]]
-        ref = oracle_lib.linear_scan(A[i], w["codes"], R, S=Sq)
-        check_topk(t2n(sub[0])[i], t2n(sub[1])[i], ref[0], ref[1])
-        certify(oracle_lib, A[i], w["codes"], t2n(sub[0])[i], t2n(sub[1])[i], pool=Sq)
-        ref = oracle_lib.query(w["cb"], w["q_host"][i], w["codes"], w["coarse"], w["off"], w["lids"], R, L, 0)
-        assert ref[2] == 1
-        check_topk(t2n(qry[0])[i], t2n(qry[1])[i], ref[0], ref[1])
+        check_topk(sub_i[i], sub_d[i], rs[0], rs[1])
+        certify(oracle_lib, A[i], w["codes"], sub_i[i], sub_d[i], pool=Sq)
+        assert rq[2] == 1
+        check_topk(qry_i[i], qry_d[i], rq[0], rq[1])
