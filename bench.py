@@ -246,7 +246,10 @@ def main():
             shapes[f"{blocks}x{threads}thr,{lds // 1024}KB"] = round(best / 1e9, 1)
         ceiling = max(shapes.values()) * 1e9
         # look-ups the kernel actually made: a slice is 64 rows x M look-ups, an abandoned one stops after M/2
-        executed = 64.0 * (slices * M - abandoned * (M // 2)) / args.steps
+        # a slice is 64 rows x M look-ups; `abandoned` slices stopped after M/2 at the latest, `quarter` of
+        # them after M/4 already, `late` ones after 3M/4 (the last two at M = 32 only)
+        quarter, late = counters[3], counters[4]
+        executed = 64.0 * (slices * M - abandoned * (M // 2) - quarter * (M // 4) - late * (M // 4)) / args.steps
         ach = executed / (scan_avg_ms * 1e-3)
         batched = {
             "bound": "lds", "kernel": f"k_scan_w4<{M}>, {Q} queries per launch, {row_chunks} row chunk(s)", "achieved": round(ach / 1e9, 1),
@@ -255,6 +258,8 @@ def main():
             "peak_by_launch_shape": shapes,
             "lookups_executed_per_launch": executed, "lookups_algorithmic_per_launch": lookups,
             "abandoned_slice_fraction": round(abandoned / max(slices, 1), 4),
+            "abandoned_after_a_quarter_fraction": round(quarter / max(slices, 1), 4),
+            "abandoned_after_three_quarters_fraction": round(late / max(slices, 1), 4),
             "algorithmic_lookup_rate": round(lookups / (scan_avg_ms * 1e-3) / 1e9, 1),
             "launch_ms": round(scan_avg_ms, 3),
             "algorithmic_bytes_per_launch": float(Q) * N * M,

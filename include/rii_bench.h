@@ -24,12 +24,14 @@ int rii_index_set_scan_events(rii_index_t* index, void* start_event, void* stop_
  * This call returns them (counters_out[RII_SCAN_COUNTERS], host) as accumulated since the last
  * call and resets them.  Synchronous (waits for the device).
  *   [0] batched scan: slices (64 rows x one group of four queries, i.e. 64 x M table look-ups) scored
- *   [1] batched scan: slices abandoned half-way (only M/2 look-ups each were made)
+ *   [1] batched scan: slices abandoned after M/2 look-ups at the latest
+ *   [3] batched scan, M = 32: those of [1] that were abandoned after M/4 look-ups already
+ *   [4] batched scan, M = 32: slices abandoned after 3M/4 look-ups
  *   one-query scan of an M = 32 array (two planes of 16 bytes per row; the first plane is always
  *   streamed, N x 16 bytes per pass):
  *   [2] 128-byte memory lines of the second plane it fetched (a row's second half is asked for
  *       only when its first 16 look-ups leave it within the bound)
- *   [3] .. [7] unused (zero). */
+ *   [5] .. [7] unused (zero). */
 int rii_index_read_scan_counters(rii_index_t* index, uint64_t* counters_out);
 
 /* Launch shape rii_adc_scan_linear uses for a batch of Q queries on this index (so that a
