@@ -24,8 +24,9 @@ launches: first plane streamed, second-plane lines fetched on demand or streamed
 fetching (nearly) every byte: moved = algorithmic.
 `roofline_batched` -- the batched launch of the timed steps (k_scan_w4: four queries share each
 code byte, so the bound is the LDS look-up rate; `achieved` counts the look-ups the kernel really
-made -- it abandons part of them -- and `peak` is the best rate the library's look-up-only kernel
-reaches over several occupancies, measured in the same run).
+made -- it abandons part of them -- and `peak` is the best rate of conflict-free 8-byte LDS reads
+over several occupancies, measured in the same run; the rate of the scan's inner loop alone at the
+kernel's own occupancy is given beside it).
 `cpu_baseline` is the CPU oracle's linear scan timed single-threaded on a bounded sample of the
 same codes (and, beside it, on all host threads with one query each).
 """
@@ -233,19 +234,28 @@ def main():
         groups = (Q + 3) // 4
         lookups = float(groups) * N * M            # one 8-byte LDS read per code byte and group of four queries
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        shapes = {}
-        for blocks, threads, lds in LDS_CEILING_SHAPES:
-            iters = max(1, 4000 * 256 * 1024 // (blocks * threads))
+
+        def best_rate(launch):
             best = 0.0
             for _ in range(3):
                 a.record()
-                n_lk = binding.rii_bench_lds_lookups(8, blocks, threads, iters, lds)
+                n = launch()
                 b.record()
                 torch.cuda.synchronize()
-                best = max(best, n_lk / (a.elapsed_time(b) * 1e-3))
-            shapes[f"{blocks}x{threads}thr,{lds // 1024}KB"] = round(best / 1e9, 1)
-        ceiling = max(shapes.values()) * 1e9
-        # look-ups the kernel actually made: a slice is 64 rows x M look-ups, an abandoned one stops after M/2
+                best = max(best, n / (a.elapsed_time(b) * 1e-3))
+            return best
+
+        # Two ceilings, each at several occupancies: the LDS pipe's own rate of conflict-free 8-byte
+        # reads (nothing but reads), and the rate of the scan's inner loop alone (address permute,
+        # 8-byte read, add -- what the vector pipe lets through).  `peak` is the first at its best.
+        reads, loops = {}, {}
+        for blocks, threads, lds in LDS_CEILING_SHAPES:
+            iters = max(1, 4000 * 256 * 1024 // (blocks * threads))
+            name = f"{blocks}x{threads}thr,{lds // 1024}KB"
+            reads[name] = round(best_rate(lambda: binding.rii_bench_lds_reads(8, blocks, threads, iters * 4, lds)) / 1e9, 1)
+            loops[name] = round(best_rate(lambda: binding.rii_bench_lds_lookups(8, blocks, threads, iters, lds)) / 1e9, 1)
+        ceiling = max(reads.values()) * 1e9
+        own_shape = f"{LDS_CEILING_SHAPES[0][0]}x{LDS_CEILING_SHAPES[0][1]}thr,{LDS_CEILING_SHAPES[0][2] // 1024}KB"
         # a slice is 64 rows x M look-ups; `abandoned` slices stopped after M/2 at the latest, `quarter` of
         # them after M/4 already, `late` ones after 3M/4 (the last two at M = 32 only)
         quarter, late = counters[3], counters[4]
@@ -254,13 +264,16 @@ def main():
         batched = {
             "bound": "lds", "kernel": f"k_scan_w4<{M}>, {Q} queries per launch, {row_chunks} row chunk(s)", "achieved": round(ach / 1e9, 1),
             "peak": round(ceiling / 1e9, 1), "unit": "G look-ups/s", "frac": round(ach / ceiling, 4),
-            "peak_source": "best of the look-up-only kernel (rii_bench_lds_lookups, 8-byte reads) over the launch shapes listed",
-            "peak_by_launch_shape": shapes,
+            "peak_source": "best rate of conflict-free 8-byte LDS reads (rii_bench_lds_reads) over the launch shapes listed, "
+                           "measured in this run",
+            "lds_read_rate_by_launch_shape": reads, "inner_loop_rate_by_launch_shape": loops,
+            "frac_of_inner_loop_rate_at_own_occupancy": round(ach / (loops[own_shape] * 1e9), 4),
             "lookups_executed_per_launch": executed, "lookups_algorithmic_per_launch": lookups,
+            "algorithmic_lookup_rate": round(lookups / (scan_avg_ms * 1e-3) / 1e9, 1),
+            "algorithmic_frac": round(lookups / (scan_avg_ms * 1e-3) / ceiling, 4),
             "abandoned_slice_fraction": round(abandoned / max(slices, 1), 4),
             "abandoned_after_a_quarter_fraction": round(quarter / max(slices, 1), 4),
             "abandoned_after_three_quarters_fraction": round(late / max(slices, 1), 4),
-            "algorithmic_lookup_rate": round(lookups / (scan_avg_ms * 1e-3) / 1e9, 1),
             "launch_ms": round(scan_avg_ms, 3),
             "algorithmic_bytes_per_launch": float(Q) * N * M,
             "algorithmic_gbs": round(float(Q) * N * M / (scan_avg_ms * 1e-3) / 1e9, 1),
@@ -325,7 +338,10 @@ def main():
         "roofline_batched": batched,
         "cpu_baseline": cpu,
         "index": {"paper_bytes": info["paper_bytes"], "device_bytes": info["device_bytes"],
-                  "device_over_paper": round(info["device_bytes"] / info["paper_bytes"], 3), "setup_s": w["timings"]},
+                  "device_over_paper": round(info["device_bytes"] / info["paper_bytes"], 3),
+                  # with RII_OPT_GATHER_COPY = 0 (M = 32: no whole-row copy for gathered scans) the handle holds N * M bytes less
+                  "device_over_paper_without_gather_copy": round((info["device_bytes"] - (N * M if M == 32 else 0)) / info["paper_bytes"], 3),
+                  "setup_s": w["timings"]},
     }
     print(json.dumps(line), flush=True)
 

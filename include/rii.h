@@ -92,8 +92,8 @@ int rii_index_create(const float* codebooks, int D, int M, int Ks, rii_index_t**
  * in ascending identifier order.
  *   codes [n][M] uint8, in host or device memory as `mem` says (RII_MEM_*).
  * Device memory held per code: M bytes, 2 M for M = 32 (which keeps the codes in two layouts, one
- * for sequential and one for gathered scans), plus M + 8 once posting lists are installed
- * (list-ordered copy, identifier, a(n)); rii_index_info reports the total.
+ * for sequential and one for gathered scans, unless RII_OPT_GATHER_COPY is 0), plus M + 4 once
+ * posting lists are installed (list-ordered copy, identifier); rii_index_info reports the total.
  * Synchronous.  If the codes were stored but re-listing them failed (RII_ERR_OOM, RII_ERR_DEVICE), the
  * index keeps the codes and is left without posting lists. */
 int rii_index_add(rii_index_t* index, const uint8_t* codes, int64_t n, int mem);

@@ -53,6 +53,12 @@ int rii_scan_linear_plan(const rii_index_t* index, int Q, int topk, int* queries
  * Look-ups performed = blocks * threads * 32 * iters. */
 int rii_bench_lds_lookups(int width, int blocks, int threads, int iters, int lds_bytes, uint32_t* sink, void* stream);
 
+/* The LDS pipe's own read ceiling, beside the look-up ceiling above: the same launch shape, but
+ * every lane only reads -- `width` = 4, 8 or 16 bytes (ds_read_b32 / _b64 / _b128) at conflict-free
+ * addresses, 16 / 8 / 4 reads in flight per wave, one exclusive-or per returned dword, no address
+ * arithmetic.  Reads performed = blocks * threads * iters * (16, 8 or 4 for width 4, 8, 16). */
+int rii_bench_lds_reads(int width, int blocks, int threads, int iters, int lds_bytes, uint32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -369,6 +369,14 @@ def rii_bench_lds_lookups(width: int, blocks: int, threads: int, iters: int, lds
     return blocks * threads * 32 * iters
 
 
+def rii_bench_lds_reads(width: int, blocks: int, threads: int, iters: int, lds_bytes: int = 64 * 1024) -> int:
+    """Measurement aid: launch the LDS read ceiling kernel on the current stream; returns the number of reads."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    _check(load_library().rii_bench_lds_reads(width, blocks, threads, iters, lds_bytes, _dp(sink), _stream()),
+           "rii_bench_lds_reads")
+    return blocks * threads * iters * {4: 16, 8: 8, 16: 4}[width]
+
+
 def rii_index_set_scan_events(index: Index, start_event, stop_event):
     """Measurement aid: raw hipEvent_t handles (ints or None) recorded around the linear-scan kernel."""
     s = ctypes.c_void_p(start_event) if start_event else None

@@ -22,6 +22,7 @@ extern "C" int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* c
                                           const uint8_t* super, int G, const float* radius, const uint8_t* coarse_g,
                                           const int32_t* perm_g, const int32_t* group_off, int32_t* assign_out,
                                           unsigned long long* visited_total, hipStream_t st);
+extern "C" int rii_internal_assign_from_lists(const rii_index* idx, int32_t* d_out, hipStream_t st);
 extern "C" int rii_internal_spread_ids(int32_t* ids, int64_t* offsets, int nq, int64_t S, int64_t N, hipStream_t st);
 extern "C" int rii_internal_copy_rows(const uint8_t* in, int64_t in_rot, int64_t in_plane, const int32_t* ids,
                                       int64_t n, int M, uint8_t* out, int64_t out_rot, int64_t out_plane,
@@ -45,7 +46,6 @@ void drop_lists(rii_index* idx) {
   free_dev(idx->d_coarse_st);
   free_dev(idx->d_list_off);
   free_dev(idx->d_list_ids);
-  free_dev(idx->d_assign);
   free_dev(idx->d_codes_list);
   idx->h_coarse.clear();
   idx->h_list_off.clear();
@@ -63,7 +63,6 @@ int install_lists(rii_index* idx, const uint8_t* coarse, int K, const std::vecto
   RII_HIP(hipMalloc(&idx->d_coarse_st, (size_t)K * M));
   RII_HIP(hipMalloc(&idx->d_list_off, (size_t)(K + 1) * 8));
   RII_HIP(hipMalloc(&idx->d_list_ids, std::max<size_t>((size_t)N * 4, 4)));
-  RII_HIP(hipMalloc(&idx->d_assign, std::max<size_t>((size_t)N * 4, 4)));
   RII_HIP(hipMalloc(&idx->d_codes_list, std::max<size_t>((size_t)N * M, 16)));
   RII_HIP(hipMemcpy(idx->d_coarse, coarse, (size_t)K * M, hipMemcpyHostToDevice));
   idx->plane_coarse = plane_for(M, K);
@@ -73,7 +72,6 @@ int install_lists(rii_index* idx, const uint8_t* coarse, int K, const std::vecto
   RII_HIP(hipMemcpy(idx->d_list_off, off.data(), (size_t)(K + 1) * 8, hipMemcpyHostToDevice));
   if (N > 0) {
     RII_HIP(hipMemcpy(idx->d_list_ids, ids.data(), (size_t)N * 4, hipMemcpyHostToDevice));
-    RII_HIP(hipMemcpy(idx->d_assign, assign.data(), (size_t)N * 4, hipMemcpyHostToDevice));
     // row p of the list-ordered copy = code of identifier list_ids[p], stored form (rotated by p)
     rc = rii_internal_copy_rows(idx->d_codes, 0, idx->plane_codes, idx->d_list_ids, N, M, idx->d_codes_list, 0,
                                 idx->plane_list, nullptr);
@@ -425,7 +423,7 @@ int rii_index_info(const rii_index_t* idx, int64_t* info) {
   info[6] = (N + K) * M + 4 * N;
   int64_t dev = (int64_t)M * 256 * idx->Ds * 4 + idx->cap * M * (idx->d_codes_rows != idx->d_codes ? 2 : 1) + (int64_t)idx->ws_bytes;
   if (idx->d_sym) dev += M * 256 * 256 * 4;
-  if (K > 0) dev += K * M + (K + 1) * 8 + N * 4 /*ids*/ + N * 4 /*assign*/ + N * M /*list-ordered codes*/;
+  if (K > 0) dev += 2 * K * M + (K + 1) * 8 + N * 4 /*ids*/ + N * M /*list-ordered codes*/;
   info[7] = dev;
   return RII_OK;
 }
@@ -491,10 +489,18 @@ int rii_index_add(rii_index_t* idx, const uint8_t* codes, int64_t n, int mem) {
     // push every new identifier to the list of its nearest coarse centre; lists stay ascending
     // because new identifiers are larger than all stored ones
     std::vector<int32_t> assign(idx->N);
-    if (oldN > 0 && hipMemcpy(assign.data(), idx->d_assign, (size_t)oldN * 4, hipMemcpyDeviceToHost) != hipSuccess) {
-      (void)hipGetLastError();
-      drop_lists(idx);
-      return RII_ERR_DEVICE;
+    if (oldN > 0) {  // a(n) of the items stored so far, read back from the lists (it is not kept)
+      idx->N = oldN;
+      DevBuf d_old;
+      int rc0 = d_old.alloc((size_t)oldN * 4);
+      if (!rc0) rc0 = rii_internal_assign_from_lists(idx, d_old.as<int32_t>(), nullptr);
+      if (!rc0 && hipMemcpy(assign.data(), d_old.p, (size_t)oldN * 4, hipMemcpyDeviceToHost) != hipSuccess) rc0 = RII_ERR_DEVICE;
+      idx->N = oldN + n;
+      if (rc0) {
+        (void)hipGetLastError();
+        drop_lists(idx);
+        return rc0;
+      }
     }
     std::vector<uint8_t> coarse = idx->h_coarse;
     const int K = idx->K;
@@ -626,7 +632,19 @@ int rii_index_get_lists(const rii_index_t* idx, uint8_t* coarse_out, int64_t* li
   if (coarse_out) RII_HIP(hipMemcpy(coarse_out, idx->d_coarse, (size_t)idx->K * idx->M, kind));
   if (list_offsets_out) RII_HIP(hipMemcpy(list_offsets_out, idx->d_list_off, (size_t)(idx->K + 1) * 8, kind));
   if (list_ids_out && idx->N) RII_HIP(hipMemcpy(list_ids_out, idx->d_list_ids, (size_t)idx->N * 4, kind));
-  if (assign_out && idx->N) RII_HIP(hipMemcpy(assign_out, idx->d_assign, (size_t)idx->N * 4, kind));
+  if (assign_out && idx->N) {
+    if (mem == RII_MEM_DEVICE) {
+      int rc = rii_internal_assign_from_lists(idx, assign_out, nullptr);
+      if (rc) return rc;
+      RII_HIP(hipDeviceSynchronize());
+    } else {
+      DevBuf tmp;
+      int rc = tmp.alloc((size_t)idx->N * 4);
+      if (!rc) rc = rii_internal_assign_from_lists(idx, tmp.as<int32_t>(), nullptr);
+      if (rc) return rc;
+      RII_HIP(hipMemcpy(assign_out, tmp.p, (size_t)idx->N * 4, hipMemcpyDeviceToHost));
+    }
+  }
   return RII_OK;
 }
 

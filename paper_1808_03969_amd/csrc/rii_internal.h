@@ -36,7 +36,6 @@ struct rii_index {
   uint8_t* d_coarse_st = nullptr; // [K][M] coarse centres, stored form (what the coarse ranking scans)
   int64_t* d_list_off = nullptr;  // [K+1]
   int32_t* d_list_ids = nullptr;  // [N] identifiers, list after list
-  int32_t* d_assign = nullptr;    // [N] a(n)
   uint8_t* d_codes_list = nullptr;  // [N][M] codes permuted into list order (row p = code of d_list_ids[p]), stored form
   std::vector<uint8_t> h_coarse;    // host mirror of the coarse centres
   std::vector<int64_t> h_list_off;  // host mirror of the list offsets

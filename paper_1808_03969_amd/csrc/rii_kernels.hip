@@ -228,11 +228,17 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
     }
     // The single-query kernel seeds the bound itself when all its blocks run at once and a query
     // has at least topk of them (rotated form only); otherwise a separate pass does it.
-    const bool seed_inside = nchunks > 1 && rot_m(M) && !batched && nchunks >= topk && nchunks <= kPrepassBlocks &&
-                             (int64_t)Q * nchunks <= kWantBlocks;
+    // ... from its blocks' minima (at most 64 kSeedPerLane blocks), or from its waves' when it
+    // has fewer than topk blocks but enough waves
+    const int waves = kScanThreads / 64;
+    const bool resident = nchunks > 1 && rot_m(M) && !batched && (int64_t)Q * nchunks <= kWantBlocks;
+    const bool seed_blocks = resident && nchunks >= topk && nchunks <= 64 * kSeedPerLane;
+    const bool seed_waves = resident && !seed_blocks && nchunks * waves >= topk && nchunks * waves <= 64 * kSeedPerLane;
+    const bool seed_inside = seed_blocks || seed_waves;
     const bool prepass = nchunks > 1 && !seed_inside;
-    a.seed_inside = seed_inside ? 1 : 0;
-    k_init_scan<<<(std::max(Q, 256) + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, minima, seed_inside ? Q * (int)nchunks : 0);
+    a.seed_inside = seed_blocks ? 1 : seed_waves ? 2 : 0;
+    const int nzero = seed_blocks ? Q * (int)nchunks : seed_waves ? Q * (int)nchunks * waves : 0;
+    k_init_scan<<<(std::max(Q, nzero) + 255) / 256, 256, 0, st>>>(tau, Q, (int)cstride, minima, nzero);
     if (timed) RII_HIP(hipEventRecord(static_cast<hipEvent_t>(idx->ev_start), st));
     a.minima = minima;
     a.counter = pre_counter;
@@ -430,6 +436,28 @@ int rii_bench_lds_lookups(int width, int blocks, int threads, int iters, int lds
     int rc = set_lds0(k_lds_lookups<4>, (size_t)lds_bytes);
     if (rc) return rc;
     k_lds_lookups<4><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
+  }
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+int rii_bench_lds_reads(int width, int blocks, int threads, int iters, int lds_bytes, uint32_t* sink, void* stream) {
+  if ((width != 4 && width != 8 && width != 16) || blocks < 1 || iters < 1 || !sink) return RII_ERR_INVALID_ARG;
+  if (threads < 64 || threads > kScanThreads || threads % 64 != 0) return RII_ERR_INVALID_ARG;
+  if (lds_bytes < 65536 || lds_bytes > 160 * 1024) return RII_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (width == 4) {
+    int rc = set_lds(k_lds_reads<4>, (size_t)lds_bytes);
+    if (rc) return rc;
+    k_lds_reads<4><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
+  } else if (width == 8) {
+    int rc = set_lds(k_lds_reads<8>, (size_t)lds_bytes);
+    if (rc) return rc;
+    k_lds_reads<8><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
+  } else {
+    int rc = set_lds(k_lds_reads<16>, (size_t)lds_bytes);
+    if (rc) return rc;
+    k_lds_reads<16><<<blocks, threads, (size_t)lds_bytes, st>>>(iters, sink);
   }
   RII_HIP(hipGetLastError());
   return RII_OK;
@@ -854,6 +882,16 @@ int rii_internal_assign_pruned(const rii_index* idx, const uint8_t* codes, int64
                   k_assign_pruned<MT><<<blocks, 256, lds, st>>>(idx->d_sym, codes, n, rot_base, plane, M, super, G, radius,
                                                                coarse_g,
                                                                perm_g, group_off, assign_out, visited_total); });
+  RII_HIP(hipGetLastError());
+  return RII_OK;
+}
+
+// a(n) of every stored item from the installed posting lists (device buffer of N entries)
+int rii_internal_assign_from_lists(const rii_index* idx, int32_t* d_out, hipStream_t st) {
+  if (idx->N == 0) return RII_OK;
+  const int64_t per = (int64_t)1 << 30;
+  if (idx->N > per * 2 - 1) return RII_ERR_UNSUPPORTED;
+  k_assign_from_lists<<<(unsigned)((idx->N + 255) / 256), 256, 0, st>>>(idx->d_list_off, idx->d_list_ids, idx->K, idx->N, d_out);
   RII_HIP(hipGetLastError());
   return RII_OK;
 }
