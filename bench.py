@@ -279,6 +279,28 @@ def main():
             "algorithmic_gbs": round(float(Q) * N * M / (scan_avg_ms * 1e-3) / 1e9, 1),
         }
 
+        # The fp16-table variant of the same kernel (same rows, same results), timed beside it.
+        out_h = (torch.empty_like(out_lin[0]), torch.empty_like(out_lin[1]))
+        binding.rii_bench_scan_linear_half(index, lut, R, out=out_h)
+        torch.cuda.synchronize()
+        rii.rii_index_set_scan_events(index, ev.start.value, ev.stop.value)
+        binding.rii_index_read_scan_counters(index)
+        half_ms = []
+        for _ in range(max(2, min(args.steps, 3))):
+            binding.rii_bench_scan_linear_half(index, lut, R, out=out_h)
+            torch.cuda.synchronize()
+            half_ms.append(ev.elapsed_ms())
+        ch = binding.rii_index_read_scan_counters(index)
+        rii.rii_index_set_scan_events(index, None, None)
+        batched["half_precision_table_variant"] = {
+            "kernel": f"k_scan_w4<{M},half>", "launch_ms": round(float(np.mean(half_ms)), 3),
+            "over_integer_table": round(float(np.mean(half_ms)) / scan_avg_ms, 4),
+            "abandoned_slice_fraction": round(ch[1] / max(ch[0], 1), 4),
+            "abandoned_after_a_quarter_fraction": round(ch[3] / max(ch[0], 1), 4),
+            "results_equal": bool(torch.equal(out_h[0], out_lin[0]) and torch.equal(out_h[1], out_lin[1])),
+        }
+        del out_h
+
     if args.pmc_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

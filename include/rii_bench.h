@@ -53,6 +53,15 @@ int rii_scan_linear_plan(const rii_index_t* index, int Q, int topk, int* queries
  * Look-ups performed = blocks * threads * 32 * iters. */
 int rii_bench_lds_lookups(int width, int blocks, int threads, int iters, int lds_bytes, uint32_t* sink, void* stream);
 
+/* rii_adc_scan_linear with the half-precision table variant of the batched kernel (Sec. 3 leaves the
+ * precision of the distance table open; the library's batched kernel filters with a 15-bit integer
+ * table, this variant with fp16 entries and packed fp16 sums; both re-score the rows that pass in
+ * fp32, so the results are the same -- what differs is the time).  Same arguments as
+ * rii_adc_scan_linear; RII_ERR_UNSUPPORTED when the batch would not take the four-queries-per-block
+ * kernel (see rii_scan_linear_plan). */
+int rii_bench_scan_linear_half(rii_index_t* index, const float* lut, int Q, int topk, int32_t* ids, float* dist,
+                               void* stream);
+
 /* The LDS pipe's own read ceiling, beside the look-up ceiling above: the same launch shape, but
  * every lane only reads -- `width` = 4, 8 or 16 bytes (ds_read_b32 / _b64 / _b128) at conflict-free
  * addresses, 16 / 8 / 4 reads in flight per wave, one exclusive-or per returned dword, no address

@@ -369,6 +369,15 @@ def rii_bench_lds_lookups(width: int, blocks: int, threads: int, iters: int, lds
     return blocks * threads * 32 * iters
 
 
+def rii_bench_scan_linear_half(index: Index, lut: torch.Tensor, topk: int, out=None):
+    """Measurement aid: rii_adc_scan_linear through the half-precision-table variant of the batched kernel."""
+    Q = lut.shape[0]
+    ids, dist = out if out is not None else _out(Q, max(topk, 1), lut.device)
+    _check(load_library().rii_bench_scan_linear_half(index.handle, _dp(lut, torch.float32), Q, topk, _dp(ids, torch.int32),
+                                                     _dp(dist, torch.float32), _stream()), "rii_bench_scan_linear_half")
+    return ids, dist
+
+
 def rii_bench_lds_reads(width: int, blocks: int, threads: int, iters: int, lds_bytes: int = 64 * 1024) -> int:
     """Measurement aid: launch the LDS read ceiling kernel on the current stream; returns the number of reads."""
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")

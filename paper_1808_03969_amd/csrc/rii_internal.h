@@ -45,6 +45,7 @@ struct rii_index {
   mutable void* ws = nullptr;
   mutable size_t ws_bytes = 0;
 
+  bool bench_half_table = false;  // set around one launch by rii_bench_scan_linear_half only
   // optional measurement aid: events recorded right before / after the linear-scan kernel
   void* ev_start = nullptr;
   void* ev_stop = nullptr;

@@ -16,6 +16,7 @@
 // identifier) order, so selection is exact and deterministic including ties.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 
 #include <algorithm>
 #include <cstdio>
@@ -260,19 +261,34 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
       // (no seeding pass for a large batch that is chunked for the cache's sake: its first chunk's
       // blocks find their bounds as an unchunked scan does, the later ones read the query's bound)
       const bool pre4 = bchunks > 1 && (Q + 3) / 4 < 2 * kWantBlocks;
-      switch (M) {
-        case 8: { int rc = set_lds0(k_scan_w4<8>, lds4); if (rc) return rc;
-                  if (pre4) { rc = set_lds0(k_tau0<8, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
-                              k_tau0<8, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
-                  k_scan_w4<8><<<g4, kScanThreads, lds4, st>>>(a4); } break;
-        case 16: { int rc = set_lds0(k_scan_w4<16>, lds4); if (rc) return rc;
-                   if (pre4) { rc = set_lds0(k_tau0<16, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
-                               k_tau0<16, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
-                   k_scan_w4<16><<<g4, kScanThreads, lds4, st>>>(a4); } break;
-        default: { int rc = set_lds0(k_scan_w4<32>, lds4); if (rc) return rc;
-                   if (pre4) { rc = set_lds0(k_tau0<32, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
-                               k_tau0<32, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); }
-                   k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+      if (pre4) {
+        switch (M) {
+          case 8: { int rc = set_lds0(k_tau0<8, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
+                    k_tau0<8, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); } break;
+          case 16: { int rc = set_lds0(k_tau0<16, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
+                     k_tau0<16, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); } break;
+          default: { int rc = set_lds0(k_tau0<32, kLinear>, tau0_lds(M) + kBlockVarsBytes); if (rc) return rc;
+                     k_tau0<32, kLinear><<<pgrid, kScanThreads, tau0_lds(M) + kBlockVarsBytes, st>>>(pre); } break;
+        }
+      }
+      if (idx->bench_half_table) {  // the separately evaluated half-precision table (measurement entry point only)
+        switch (M) {
+          case 8: { int rc = set_lds0(k_scan_w4<8, true>, lds4); if (rc) return rc;
+                    k_scan_w4<8, true><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+          case 16: { int rc = set_lds0(k_scan_w4<16, true>, lds4); if (rc) return rc;
+                     k_scan_w4<16, true><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+          default: { int rc = set_lds0(k_scan_w4<32, true>, lds4); if (rc) return rc;
+                     k_scan_w4<32, true><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+        }
+      } else {
+        switch (M) {
+          case 8: { int rc = set_lds0(k_scan_w4<8>, lds4); if (rc) return rc;
+                    k_scan_w4<8><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+          case 16: { int rc = set_lds0(k_scan_w4<16>, lds4); if (rc) return rc;
+                     k_scan_w4<16><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+          default: { int rc = set_lds0(k_scan_w4<32>, lds4); if (rc) return rc;
+                     k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a4); } break;
+        }
       }
     } else if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2 && topk > kWaveK4) {
       // Large batch with topk beyond the four-query kernel's reach: two queries per block
@@ -439,6 +455,20 @@ int rii_bench_lds_lookups(int width, int blocks, int threads, int iters, int lds
   }
   RII_HIP(hipGetLastError());
   return RII_OK;
+}
+
+int rii_bench_scan_linear_half(rii_index_t* idx, const float* lut, int Q, int topk, int32_t* ids, float* dist,
+                               void* stream) {
+  if (!idx) return RII_ERR_INVALID_ARG;
+  int qpb = 0;
+  int64_t chunks = 0;
+  int rc = rii_scan_linear_plan(idx, Q, topk, &qpb, &chunks);
+  if (rc) return rc;
+  if (qpb != 4) return RII_ERR_UNSUPPORTED;  // only the four-queries-per-block kernel has the variant
+  idx->bench_half_table = true;
+  rc = rii_adc_scan_linear(idx, lut, Q, topk, ids, dist, stream);
+  idx->bench_half_table = false;
+  return rc;
 }
 
 int rii_bench_lds_reads(int width, int blocks, int threads, int iters, int lds_bytes, uint32_t* sink, void* stream) {

@@ -311,6 +311,47 @@ def test_reserve_workspace_then_no_growth(rii, oracle_lib, idx16):
         check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
 
 
+@pytest.mark.parametrize("M,kind", [(8, "uniform"), (16, "clustered"), (32, "uniform"), (32, "clustered")])
+def test_half_precision_table_variant(M, kind, rii, oracle_lib):
+    """The separately evaluated variant of the batched kernel whose filter table holds fp16 entries
+    (packed fp16 sums) instead of 15-bit integers: rows that pass are re-scored in fp32 as in the
+    library's kernel, so the result must equal the oracle's bit for bit -- the filter may only let
+    too many rows through, never too few.  Large-magnitude and tiny tables included (the scale of
+    the fp16 table is a power of two chosen per group of four queries)."""
+    from paper_1808_03969_amd import binding
+    N, Q, topk = 150_003, 270, 50  # 68 groups of four: enough blocks for the batched kernel, last group short
+    rng = np.random.default_rng(900 + M)
+    cb = rng.normal(size=(M, 256, 2)).astype(np.float32)
+    if kind == "uniform":
+        codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+    else:  # a few hundred distinct prototypes with some bytes changed: near-ties and long equal prefixes
+        proto = rng.integers(0, 256, size=(300, M), dtype=np.uint8)
+        codes = proto[rng.integers(0, 300, size=N)]
+        flip = rng.random(size=(N, M)) < 0.1
+        codes[flip] = rng.integers(0, 256, size=int(flip.sum()), dtype=np.uint8)
+    q = rng.normal(size=(Q, 2 * M)).astype(np.float32)
+    q[4:8] *= 1000.0   # one group of four with large distances,
+    q[8:12] *= 1e-3    # one with the queries near the origin,
+    q[13] *= 300.0     # one group of mixed magnitudes
+    index = rii.Index(cb)
+    index.add(codes)
+    lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+    A = oracle_lib.lut(cb, q)
+    assert binding.rii_scan_linear_plan(index, Q, topk)[0] == 4
+    ids, dist = binding.rii_bench_scan_linear_half(index, lut, topk)
+    torch.cuda.synchronize()
+    ids, dist = t2n(ids), t2n(dist)
+    for i in range(Q):
+        ref = oracle_lib.linear_scan(A[i], codes, topk)
+        assert np.array_equal(ids[i], ref[0]) and np.array_equal(dist[i], ref[1]), (M, kind, i)
+    # the library's own kernel on the same call (the flag does not stick)
+    ids2, dist2 = rii.rii_adc_scan_linear(index, lut, topk)
+    torch.cuda.synchronize()
+    assert np.array_equal(t2n(ids2), ids) and np.array_equal(t2n(dist2), dist)
+    with pytest.raises(rii.RiiError):
+        binding.rii_bench_scan_linear_half(index, lut[:2].contiguous(), topk)  # not a four-queries-per-block launch
+
+
 @pytest.mark.parametrize("M,Q,topk", [(8, 263, 100), (16, 258, 10)])
 def test_linear_scan_large_batch_in_row_chunks(M, Q, topk, rii, oracle_lib):
     """A batch that takes the several-queries-per-block kernel, over a code array long enough to
