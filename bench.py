@@ -70,6 +70,50 @@ class HipEvents:
         return float(ms.value)
 
 
+SWEEP_SHAPES = [  # (M, N): every one with the (Q, topk) pairs below
+    (32, 100_000_000), (64, 50_000_000), (16, 10_000_000), (64, 5_000_000),
+]
+SWEEP_BATCHES = [(1, 100), (1, 129), (1, 256), (1, 1024), (64, 100), (64, 256), (64, 1024), (1024, 100), (1024, 1024)]
+
+
+def sweep(rii, np, torch):
+    """Launch time of rii_adc_scan_linear by shape (best of three calls, torch events around the
+    call; uniform random codes and Gaussian code books, so nothing is pruned by the data)."""
+    from paper_1808_03969_amd import binding
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for M, N in SWEEP_SHAPES:
+        rng = np.random.default_rng(5 + M)
+        index = rii.Index(rng.normal(size=(M, 256, 2)).astype(np.float32))
+        if M == 32:
+            index.set_option(binding.RII_OPT_GATHER_COPY, 0)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(5 + M)
+        for r0 in range(0, N, 10_000_000):
+            n = min(N, r0 + 10_000_000) - r0
+            index.add(torch.randint(0, 256, (n, M), dtype=torch.uint8, device="cuda", generator=gen))
+        lut = rii.rii_build_lut(index, torch.from_numpy(rng.normal(size=(1024, 2 * M)).astype(np.float32)).cuda())
+        for Q, topk in SWEEP_BATCHES:
+            if Q * N > 12_000_000_000 and (topk > 100 or M == 64):
+                continue  # (seconds per call on the one-query-per-block paths)
+            l = lut[:Q].contiguous()
+            qpb, chunks = binding.rii_scan_linear_plan(index, Q, topk)
+            rii.rii_adc_scan_linear(index, l, topk)
+            torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(3):
+                a.record()
+                rii.rii_adc_scan_linear(index, l, topk)
+                b.record()
+                torch.cuda.synchronize()
+                best = min(best, a.elapsed_time(b))
+            print(json.dumps({"M": M, "N": N, "Q": Q, "topk": topk, "queries_per_block": qpb, "row_chunks": chunks,
+                              "ms": round(best, 4), "codes_per_s": round(Q * N / (best * 1e-3), 1),
+                              "algorithmic_gbs": round(Q * N * M / (best * 1e-3) / 1e9, 1)}), flush=True)
+        index.close()
+        del index, lut
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,6 +129,10 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain streaming kernel of known size (1 GiB read + 1 GiB written) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the bench step: time rii_adc_scan_linear over uniform random codes for a set of "
+                         "(M, N, Q, topk) shapes, including those outside the fast kernels' reach (M = 64, topk > 128); "
+                         "one JSON line per shape")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (queries and codes would shard "
@@ -100,6 +148,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     rii.load_library()
     torch.cuda.set_device(0)
+    if args.sweep:
+        sweep(rii, np, torch)
+        return
     cfg = workloads.CONFIGS[args.workload]
     t_setup = time.time()
     w = workloads.build(cfg, log=log, N=args.n, Q=args.queries)
@@ -301,6 +352,24 @@ def main():
         }
         del out_h
 
+    # The subset scan gathers rows of M bytes out of 128-byte memory lines: bytes it needs against
+    # the bytes of the lines they lie in (counted from the identifiers of a sample of the queries).
+    toff_h = toff[:17].cpu().numpy()
+    rows_per_line = max(1, 128 // M)
+    n_lines = 0
+    for i in range(len(toff_h) - 1):
+        n_lines += int(torch.unique(tids[toff_h[i]:toff_h[i + 1]] // rows_per_line).numel())
+    sampled = int(toff_h[-1] - toff_h[0])
+    useful = float(Q) * S * (M + 4)
+    in_lines = (n_lines * 128.0 / max(sampled, 1) + 4.0) * Q * S
+    subset = {
+        "kernel": f"k_scan_w<{M},subset>, {Q} queries x {S} target identifiers", "launch_ms": round(float(stage_ms[4]), 3),
+        "useful_bytes": useful, "useful_gbs": round(useful / (stage_ms[4] * 1e-3) / 1e9, 1),
+        "bytes_of_the_lines_touched": in_lines, "line_gbs": round(in_lines / (stage_ms[4] * 1e-3) / 1e9, 1),
+        "note": "a gathered row brings its whole 128-byte line (identifiers: 4 bytes each, read in sequence); when the "
+                "code array fits the caches (small N) the lines come from there and line_gbs can exceed the HBM rate",
+    }
+
     if args.pmc_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -358,6 +427,7 @@ def main():
         "roofline": roofline,
         "roofline_no_pruning": no_pruning,
         "roofline_batched": batched,
+        "subset_scan": subset,
         "cpu_baseline": cpu,
         "index": {"paper_bytes": info["paper_bytes"], "device_bytes": info["device_bytes"],
                   "device_over_paper": round(info["device_bytes"] / info["paper_bytes"], 3),
