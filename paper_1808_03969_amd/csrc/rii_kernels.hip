@@ -213,7 +213,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
   if (Q > 65535) return RII_ERR_UNSUPPORTED;
   const bool timed = mode == kLinear && idx->ev_start && idx->ev_stop && codes == idx->d_codes;
   a.counters = timed ? idx->d_scan_counters : nullptr;
-  if (topk <= kWaveK) {
+  if (topk <= kWaveK || rot_m(M)) {  // (rotated stored form: k_scan_w up to RII_MAX_TOPK, with a block-level buffer above kWaveK)
     // When a query's rows are split over several blocks, a short first pass over the leading
     // rows seeds the shared bound, so that the main pass starts with few candidates.
     const int64_t tile_rows = (int64_t)kScanThreads * kRowsPerLane;
@@ -290,7 +290,7 @@ int launch_scan(const rii_index* idx, const uint8_t* codes, int64_t plane, int64
                      k_scan_w4<32><<<g4, kScanThreads, lds4, st>>>(a4); } break;
         }
       }
-    } else if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2 && topk > kWaveK4) {
+    } else if (mode == kLinear && rot_m(M) && nchunks == 1 && !qmode && Q >= 2 && topk > kWaveK4 && topk <= kWaveK) {
       // Large batch with topk beyond the four-query kernel's reach: two queries per block
       // (k_scan_w2), every block owning its queries' whole scan, and a single-query block for an
       // odd one left over, addressed as query 0 of argument arrays shifted by Q - 1.

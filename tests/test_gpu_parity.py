@@ -311,6 +311,56 @@ def test_reserve_workspace_then_no_growth(rii, oracle_lib, idx16):
         check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
 
 
+@pytest.mark.parametrize("M", [16, 32])
+def test_linear_scan_large_topk_block_buffer(M, rii, oracle_lib):
+    """topk above the per-wave buffers' reach: the waves of a block share one candidate buffer and
+    compact it together whenever it fills.  Rows stored in order of DEcreasing distance to query 0
+    make every row a candidate when it is met, so the buffer fills again and again and waves join
+    compactions from every point of their loop (and after their rows have run out); query 1 meets
+    the same rows in random order; target lists of uneven length take the same path."""
+    N, Q = 1_300_000 + 77, 16  # 16 blocks per query, ~80k rows (20 tiles) each
+    rng = np.random.default_rng(640 + M)
+    cb = rng.normal(size=(M, 256, 2)).astype(np.float32)
+    codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+    q = rng.normal(size=(Q, 2 * M)).astype(np.float32)
+    q[1] = q[0] * 1.01  # nearly the same order of rows for query 1
+    A = oracle_lib.lut(cb, q)
+    full = oracle_lib.linear_scan(A[0], codes, N)       # all rows in (distance, id) order
+    codes = np.ascontiguousarray(codes[full[0][::-1]])  # farthest first
+    index = rii.Index(cb)
+    index.add(codes)
+    lut = rii.rii_build_lut(index, torch.from_numpy(q).cuda())
+    for topk in (129, 1000, 1024):
+        ids, dist = rii.rii_adc_scan_linear(index, lut, topk)
+        torch.cuda.synchronize()
+        for i in range(Q):
+            ref = oracle_lib.linear_scan(A[i], codes, topk)
+            assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), (M, topk, i)
+    lut = lut[:2].contiguous()
+    tids, toff = synth.subset_batch(91, N, [N - 5, 1500])
+    sub = rii.rii_adc_scan_subset(index, lut, tids.cuda(), toff.cuda(), N, 700)
+    torch.cuda.synchronize()
+    tids, toff = t2n(tids), t2n(toff)
+    for i in range(2):
+        ref = oracle_lib.linear_scan(A[i], codes, 700, S=tids[toff[i]:toff[i + 1]])
+        assert np.array_equal(t2n(sub[0])[i], ref[0]) and np.array_equal(t2n(sub[1])[i], ref[1]), (M, "subset", i)
+    # one block per query (a short array), fewer rows than topk in one of them
+    small = rii.Index(cb)
+    small.add(codes[:5000])
+    ids, dist = rii.rii_adc_scan_linear(small, lut, 1024)
+    torch.cuda.synchronize()
+    for i in range(2):
+        ref = oracle_lib.linear_scan(A[i], codes[:5000], 1024)
+        assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])
+    tiny = rii.Index(cb)
+    tiny.add(codes[:300])
+    ids, dist = rii.rii_adc_scan_linear(tiny, lut, 512)
+    torch.cuda.synchronize()
+    for i in range(2):
+        ref = oracle_lib.linear_scan(A[i], codes[:300], 512)
+        check_topk(t2n(ids)[i], t2n(dist)[i], ref[0], ref[1])
+
+
 @pytest.mark.parametrize("M,kind", [(8, "uniform"), (16, "clustered"), (32, "uniform"), (32, "clustered")])
 def test_half_precision_table_variant(M, kind, rii, oracle_lib):
     """The separately evaluated variant of the batched kernel whose filter table holds fp16 entries
