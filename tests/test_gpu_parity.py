@@ -196,6 +196,23 @@ def test_linear_scan_ties_and_padding(rii, oracle_lib):
     for i in range(6):
         ref = oracle_lib.linear_scan(A[i], codes, 700)
         assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1])
+    # the same ties against the per-wave buffers (topk <= 128): a full buffer of equal distances
+    # cannot make room by a distance bound alone and falls back to sorting; one query per block ...
+    for topk in (100, 128):
+        ids, dist = rii.rii_adc_scan_linear(index, lut, topk)
+        torch.cuda.synchronize()
+        for i in range(6):
+            ref = oracle_lib.linear_scan(A[i], codes, topk)
+            assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), (topk, i)
+    # ... and four queries per block (a batch large enough for that kernel)
+    qb = rng.normal(size=(300, 32)).astype(np.float32)
+    lutb = rii.rii_build_lut(index, torch.from_numpy(qb).cuda())
+    Ab = oracle_lib.lut(cb, qb)
+    ids, dist = rii.rii_adc_scan_linear(index, lutb, 100)
+    torch.cuda.synchronize()
+    for i in range(0, 300, 7):
+        ref = oracle_lib.linear_scan(Ab[i], codes, 100)
+        assert np.array_equal(t2n(ids)[i], ref[0]) and np.array_equal(t2n(dist)[i], ref[1]), ("batched", i)
     small = rii.Index(cb)
     small.add(codes[:5])
     ids, dist = rii.rii_adc_scan_linear(small, lut, 8)
