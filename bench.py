@@ -314,6 +314,9 @@ def main():
         ach = executed / (scan_avg_ms * 1e-3)
         batched = {
             "bound": "lds", "kernel": f"k_scan_w4<{M}>, {Q} queries per launch, {row_chunks} row chunk(s)", "achieved": round(ach / 1e9, 1),
+            "bound_note": "the unit of work is an 8-byte LDS read per code byte and group of four queries; SQ counters "
+                          "(profiles/k_scan_w4_k_scan_w_c5_instruction_mix_pmc.txt) show the vector pipe, not the LDS pipe, "
+                          "as the busiest unit of this kernel",
             "peak": round(ceiling / 1e9, 1), "unit": "G look-ups/s", "frac": round(ach / ceiling, 4),
             "peak_source": "best rate of conflict-free 8-byte LDS reads (rii_bench_lds_reads) over the launch shapes listed, "
                            "measured in this run",
